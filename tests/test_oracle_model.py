@@ -1,0 +1,370 @@
+"""Pins for oracle/model.py.  Nothing here re-uses the oracle to produce an expected value:
+expectations come from torch library routines, closed forms, hand-written fixtures and
+brute-force scalar loops."""
+import json
+import math
+import os
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from workloads import ModelCfg, gen_weights, gen_tokens, gen_uniform_tree, gen_chain_tree
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _np_weights(w):
+    f = lambda t: t.double().numpy()
+    return dict(embed=f(w["embed"]), final_norm=f(w["final_norm"]), lm_head=f(w["lm_head"]),
+                layers=[{k: f(v) for k, v in lw.items()} for lw in w["layers"]])
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    cfg = ModelCfg(2, 64, 4, 2, 16, 96, 50, dtype="fp32")     # GQA 4/2 on purpose
+    w = _np_weights(gen_weights(cfg, seed=11))
+    # make activations O(1) so that softmax and silu are exercised away from their linear regime
+    for lw in w["layers"]:
+        for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            lw[k] = lw[k] * 8.0
+    w["embed"] = w["embed"] * 50.0
+    w["lm_head"] = w["lm_head"] * 8.0
+    return cfg, w
+
+
+# ---------------------------------------------------------------------------------------
+# tree bookkeeping against the hand-written fixture
+# ---------------------------------------------------------------------------------------
+
+def test_tree_fixture_depths_and_paths():
+    g = json.load(open(os.path.join(GOLD, "tree_small.json")))
+    par = np.array(g["parent"])
+    assert oracle.tree_depths(par).tolist() == g["depth"]
+    for i, p in enumerate(g["path"]):
+        assert oracle.ancestors(par, i) == p
+
+
+def test_tree_depths_rejects_bad_order():
+    with pytest.raises(ValueError):
+        oracle.tree_depths(np.array([-1, 2, 1]))
+
+
+# ---------------------------------------------------------------------------------------
+# RoPE: fixture values, complex-multiplication form, relative-position property
+# ---------------------------------------------------------------------------------------
+
+def test_rope_fixture():
+    g = json.load(open(os.path.join(GOLD, "rope_case.json")))
+    for c in g["cases"]:
+        y = oracle.rope(np.array(c["x"]).reshape(1, 1, -1), [c["pos"]], g["base"])
+        np.testing.assert_allclose(y.reshape(-1), c["y"], atol=1e-15)
+
+
+def test_rope_is_complex_rotation():
+    r = np.random.default_rng(0)
+    x = r.standard_normal((5, 3, 8))
+    pos = np.array([0, 1, 7, 100, 4095])
+    y = oracle.rope(x, pos, 10000.0)
+    z = x[..., :4] + 1j * x[..., 4:]
+    ang = pos[:, None] * (10000.0 ** (-np.arange(4) * 2 / 8))[None, :]
+    zr = z * np.exp(1j * ang)[:, None, :]
+    np.testing.assert_allclose(y[..., :4], zr.real, atol=1e-12)
+    np.testing.assert_allclose(y[..., 4:], zr.imag, atol=1e-12)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    r = np.random.default_rng(1)
+    q, k = r.standard_normal((1, 1, 16)), r.standard_normal((1, 1, 16))
+    s0 = (oracle.rope(q, [9], 1e4) * oracle.rope(k, [4], 1e4)).sum()
+    s1 = (oracle.rope(q, [109], 1e4) * oracle.rope(k, [104], 1e4)).sum()
+    assert abs(s0 - s1) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------
+# RMSNorm vs the torch library routine
+# ---------------------------------------------------------------------------------------
+
+def test_rmsnorm_vs_torch():
+    r = np.random.default_rng(2)
+    x, g = r.standard_normal((7, 33)), r.standard_normal(33)
+    ref = F.rms_norm(torch.from_numpy(x), (33,), torch.from_numpy(g), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.rmsnorm(x, g, 1e-5), ref, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# attention membership: with all scores equal the output is the plain mean of V over the
+# attended set, so one-hot V rows reveal exactly which keys each node sees
+# ---------------------------------------------------------------------------------------
+
+def test_attention_membership_closed_form():
+    g = json.load(open(os.path.join(GOLD, "tree_small.json")))
+    par = np.array(g["parent"])
+    T, P, Hq, Hkv = len(par), 3, 4, 2
+    Dh = P + T
+    q = np.zeros((T, Hq, Dh))
+    eye = np.eye(Dh)
+    v_pre = np.repeat(eye[:P, None, :], Hkv, axis=1)
+    v_tree = np.repeat(eye[P:, None, :], Hkv, axis=1)
+    k_pre = np.random.default_rng(3).standard_normal((P, Hkv, Dh))
+    k_tree = np.random.default_rng(4).standard_normal((T, Hkv, Dh))
+    out = oracle.tree_attention(q, k_tree, v_tree, k_pre, v_pre, par)
+    for i in range(T):
+        attended = list(range(P)) + [P + j for j in g["path"][i]]
+        expect = np.zeros(Dh)
+        expect[attended] = 1.0 / (P + g["depth"][i] + 1)
+        for h in range(Hq):
+            np.testing.assert_allclose(out[i, h], expect, atol=1e-15)
+
+
+def test_attention_vs_torch_sdpa_with_explicit_mask():
+    """Same tree, random q/k/v: torch's scaled_dot_product_attention with a boolean mask built
+    from the fixture's hand-written paths (GQA through torch's own enable_gqa)."""
+    g = json.load(open(os.path.join(GOLD, "tree_small.json")))
+    par = np.array(g["parent"])
+    T, P, Hq, Hkv, Dh = len(par), 5, 4, 2, 8
+    r = np.random.default_rng(5)
+    q = r.standard_normal((T, Hq, Dh))
+    kt, vt = r.standard_normal((T, Hkv, Dh)), r.standard_normal((T, Hkv, Dh))
+    kp, vp = r.standard_normal((P, Hkv, Dh)), r.standard_normal((P, Hkv, Dh))
+    out = oracle.tree_attention(q, kt, vt, kp, vp, par)
+    mask = torch.zeros(T, P + T, dtype=torch.bool)
+    mask[:, :P] = True
+    for i, path in enumerate(g["path"]):
+        mask[i, [P + j for j in path]] = True
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(np.concatenate([kp, kt])).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(np.concatenate([vp, vt])).permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(out, ref, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------
+# whole decoder vs a forward assembled from torch library ops (causal case)
+# ---------------------------------------------------------------------------------------
+
+def _torch_causal_forward(cfg, w, seq):
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    n, Hq, Hkv, Dh = len(seq), cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    h = t(w["embed"])[torch.as_tensor(seq, dtype=torch.long)]
+    inv = 1.0 / (cfg.rope_base ** (torch.arange(0, Dh, 2, dtype=torch.float64) / Dh))
+    rot = torch.polar(torch.ones(n, Dh // 2, dtype=torch.float64), torch.arange(n, dtype=torch.float64)[:, None] * inv)
+
+    def rope(x):  # [n,H,Dh], complex multiply on (first half, second half)
+        z = torch.complex(x[..., :Dh // 2], x[..., Dh // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    for lw in w["layers"]:
+        x = F.rms_norm(h, (cfg.d_model,), t(lw["attn_norm"]), eps=cfg.rms_eps)
+        q = rope(F.linear(x, t(lw["wq"])).view(n, Hq, Dh)).permute(1, 0, 2)[None]
+        k = rope(F.linear(x, t(lw["wk"])).view(n, Hkv, Dh)).permute(1, 0, 2)[None]
+        v = F.linear(x, t(lw["wv"])).view(n, Hkv, Dh).permute(1, 0, 2)[None]
+        o = F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).reshape(n, Hq * Dh)
+        h = h + F.linear(o, t(lw["wo"]))
+        x = F.rms_norm(h, (cfg.d_model,), t(lw["ffn_norm"]), eps=cfg.rms_eps)
+        h = h + F.linear(F.silu(F.linear(x, t(lw["w_gate"]))) * F.linear(x, t(lw["w_up"])), t(lw["w_down"]))
+    x = F.rms_norm(h, (cfg.d_model,), t(w["final_norm"]), eps=cfg.rms_eps)
+    return F.linear(x, t(w["lm_head"])).numpy()
+
+
+def test_causal_forward_vs_torch_library(tiny):
+    cfg, w = tiny
+    seq = gen_tokens(12, cfg.vocab, seed=3)
+    ref = _torch_causal_forward(cfg, w, seq)
+    got = oracle.path_forward(cfg, w, None, None, seq, return_all=True)
+    assert np.abs(ref).max() > 0.5          # the comparison is not between zeros
+    np.testing.assert_allclose(got, ref, atol=1e-10)
+
+
+def test_chain_tree_is_causal_decoding(tiny):
+    """A chain-shaped tree after a prefilled prefix = one causal forward over prefix+chain,
+    checked against the torch-library forward (pins prefix handling and positions)."""
+    cfg, w = tiny
+    P, T = 9, 6
+    prefix = gen_tokens(P, cfg.vocab, seed=4)
+    tok, par = gen_chain_tree(T, cfg.vocab, seed=5)
+    _, pk, pv = oracle.path_forward(cfg, w, None, None, prefix, return_kv=True)
+    out = oracle.verify_tree(cfg, w, pk, pv, tok, par)
+    ref = _torch_causal_forward(cfg, w, np.concatenate([prefix, tok]))[P:]
+    np.testing.assert_allclose(out["logits"], ref, atol=1e-10)
+
+
+def test_every_node_equals_brute_force_path_forward(tiny):
+    cfg, w = tiny
+    P, T = 7, 20
+    prefix = gen_tokens(P, cfg.vocab, seed=6)
+    tok, par = gen_uniform_tree(T, cfg.vocab, seed=7)
+    _, pk, pv = oracle.path_forward(cfg, w, None, None, prefix, return_kv=True)
+    out = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    for i in range(T):
+        seq = np.concatenate([prefix, tok[oracle.ancestors(par, i)]])
+        ref = _torch_causal_forward(cfg, w, seq)[-1]
+        np.testing.assert_allclose(out[i], ref, atol=1e-10)
+        np.testing.assert_allclose(oracle.path_forward(cfg, w, pk, pv, tok[oracle.ancestors(par, i)]), ref, atol=1e-10)
+
+
+# ---------------------------------------------------------------------------------------
+# structural invariants (the paper's local-equivalence argument, Sect. 4.1)
+# ---------------------------------------------------------------------------------------
+
+def _setup(tiny, P=5, T=16, seed=8):
+    cfg, w = tiny
+    r = np.random.default_rng(seed)
+    pk = r.standard_normal((cfg.n_layers, P, cfg.n_kv_heads, cfg.head_dim))
+    pv = r.standard_normal((cfg.n_layers, P, cfg.n_kv_heads, cfg.head_dim))
+    tok, par = gen_uniform_tree(T, cfg.vocab, seed=seed)
+    return cfg, w, pk, pv, tok, par
+
+
+def test_permutation_invariance(tiny):
+    cfg, w, pk, pv, tok, par = _setup(tiny)
+    T = len(tok)
+    base = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    # another topological order: sort by (depth, reversed index)
+    depth = oracle.tree_depths(par)
+    order = sorted(range(T), key=lambda i: (depth[i], -i))
+    new_of_old = np.empty(T, dtype=int)
+    new_of_old[order] = np.arange(T)
+    tok2 = tok[order]
+    par2 = np.array([-1 if par[o] < 0 else new_of_old[par[o]] for o in order])
+    out2 = oracle.verify_tree(cfg, w, pk, pv, tok2, par2)["logits"]
+    np.testing.assert_allclose(out2, base[order], atol=1e-11)
+
+
+def test_non_ancestor_independence_and_duplicate_siblings(tiny):
+    cfg, w, pk, pv, tok, par = _setup(tiny, seed=9)
+    base = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    j = 6
+    tok2 = tok.copy()
+    tok2[j] = (tok[j] + 1) % cfg.vocab
+    out2 = oracle.verify_tree(cfg, w, pk, pv, tok2, par)["logits"]
+    for i in range(len(tok)):
+        if j in oracle.ancestors(par, i):
+            assert np.abs(out2[i] - base[i]).max() > 1e-9
+        else:
+            assert np.array_equal(out2[i], base[i])
+    # two children of one parent with the same token get the same row
+    tok3, par3 = np.append(tok, tok[5]), np.append(par, par[5])
+    out3 = oracle.verify_tree(cfg, w, pk, pv, tok3, par3)["logits"]
+    np.testing.assert_allclose(out3[-1], out3[5], atol=1e-12)   # BLAS may block a T+1 batch differently
+
+
+def test_single_node_tree_is_single_token_decode(tiny):
+    cfg, w, pk, pv, tok, par = _setup(tiny, T=1)
+    out = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    ref = oracle.path_forward(cfg, w, pk, pv, tok)
+    np.testing.assert_allclose(out[0], ref, atol=1e-11)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads(tiny):
+    cfg, w, pk, pv, tok, par = _setup(tiny, seed=10)
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    cfg2 = ModelCfg(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_q_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab)
+    w2 = dict(w, layers=[dict(lw) for lw in w["layers"]])
+    for lw in w2["layers"]:
+        for k in ("wk", "wv"):
+            m = lw[k].reshape(cfg.n_kv_heads, cfg.head_dim, cfg.d_model)
+            lw[k] = np.repeat(m, G, axis=0).reshape(-1, cfg.d_model)
+    a = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    b = oracle.verify_tree(cfg2, w2, np.repeat(pk, G, axis=2), np.repeat(pv, G, axis=2), tok, par)["logits"]
+    np.testing.assert_allclose(a, b, atol=1e-11)
+
+
+def test_zero_weights_give_zero_logits(tiny):
+    cfg, w, pk, pv, tok, par = _setup(tiny)
+    w0 = dict(w, lm_head=np.zeros_like(w["lm_head"]))
+    assert np.all(oracle.verify_tree(cfg, w0, pk, pv, tok, par)["logits"] == 0.0)
+
+
+def test_adding_a_constant_to_all_positions_changes_nothing(tiny):
+    """RoPE makes scores depend on position differences only: re-rotating the prefix keys by
+    +delta and shifting every tree position by +delta leaves the logits unchanged.  The shift is
+    realised by prepending delta dummy prefix tokens that carry zero V and very negative scores is
+    not possible generically, so the property is checked on the prefilled cache instead: a prefix
+    cache prefilled from tokens at positions 0..P-1 equals, after rotation by delta, the cache of
+    the same tokens prefilled at delta..delta+P-1 for the attention scores."""
+    cfg, w = tiny
+    r = np.random.default_rng(12)
+    q = r.standard_normal((1, cfg.n_q_heads, cfg.head_dim))
+    k = r.standard_normal((4, cfg.n_kv_heads, cfg.head_dim))
+    for delta in (1, 50):
+        s0 = np.einsum("hd,jhd->hj", oracle.rope(q, [10], 1e4)[0], np.repeat(oracle.rope(k, np.arange(4), 1e4), 2, axis=1))
+        s1 = np.einsum("hd,jhd->hj", oracle.rope(q, [10 + delta], 1e4)[0], np.repeat(oracle.rope(k, np.arange(4) + delta, 1e4), 2, axis=1))
+        np.testing.assert_allclose(s0, s1, atol=1e-11)
+
+
+# ---------------------------------------------------------------------------------------
+# brute force with scalar loops on a toy decoder (no numpy linear algebra)
+# ---------------------------------------------------------------------------------------
+
+def _scalar_forward(cfg, w, seq):
+    d, H, Dh, Fh, V = cfg.d_model, cfg.n_q_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab
+    assert cfg.n_kv_heads == H
+    n = len(seq)
+    h = [[float(w["embed"][seq[s]][c]) for c in range(d)] for s in range(n)]
+
+    def norm(vec, g):
+        ms = sum(v * v for v in vec) / len(vec)
+        return [v / math.sqrt(ms + cfg.rms_eps) * float(g[c]) for c, v in enumerate(vec)]
+
+    def lin(vec, W):
+        return [sum(float(W[o][c]) * vec[c] for c in range(len(vec))) for o in range(len(W))]
+
+    def rot(vec, pos):
+        out = list(vec)
+        for hh in range(H):
+            for i in range(Dh // 2):
+                th = pos * cfg.rope_base ** (-2.0 * i / Dh)
+                a, b = vec[hh * Dh + i], vec[hh * Dh + i + Dh // 2]
+                out[hh * Dh + i] = a * math.cos(th) - b * math.sin(th)
+                out[hh * Dh + i + Dh // 2] = a * math.sin(th) + b * math.cos(th)
+        return out
+
+    for lw in w["layers"]:
+        xs = [norm(h[s], lw["attn_norm"]) for s in range(n)]
+        qs = [rot(lin(xs[s], lw["wq"]), s) for s in range(n)]
+        ks = [rot(lin(xs[s], lw["wk"]), s) for s in range(n)]
+        vs = [lin(xs[s], lw["wv"]) for s in range(n)]
+        for s in range(n):
+            o = [0.0] * (H * Dh)
+            for hh in range(H):
+                sc = [sum(qs[s][hh * Dh + c] * ks[j][hh * Dh + c] for c in range(Dh)) / math.sqrt(Dh) for j in range(s + 1)]
+                m = max(sc)
+                e = [math.exp(v - m) for v in sc]
+                z = sum(e)
+                for c in range(Dh):
+                    o[hh * Dh + c] = sum(e[j] / z * vs[j][hh * Dh + c] for j in range(s + 1))
+            upd = lin(o, lw["wo"])
+            h[s] = [h[s][c] + upd[c] for c in range(d)]
+        for s in range(n):
+            x = norm(h[s], lw["ffn_norm"])
+            gt, up = lin(x, lw["w_gate"]), lin(x, lw["w_up"])
+            a = [gt[c] / (1.0 + math.exp(-gt[c])) * up[c] for c in range(Fh)]
+            upd = lin(a, lw["w_down"])
+            h[s] = [h[s][c] + upd[c] for c in range(d)]
+    return [lin(norm(h[s], w["final_norm"]), w["lm_head"]) for s in range(n)]
+
+
+def test_toy_decoder_vs_scalar_loops():
+    cfg = ModelCfg(2, 8, 2, 2, 4, 6, 5)
+    r = np.random.default_rng(13)
+    mk = lambda *s: r.standard_normal(s)
+    w = dict(embed=mk(5, 8), final_norm=1 + 0.1 * mk(8), lm_head=mk(5, 8),
+             layers=[dict(attn_norm=1 + 0.1 * mk(8), wq=mk(8, 8), wk=mk(8, 8), wv=mk(8, 8), wo=mk(8, 8),
+                          ffn_norm=1 + 0.1 * mk(8), w_gate=mk(6, 8), w_up=mk(6, 8), w_down=mk(8, 6)) for _ in range(2)])
+    seq = [3, 1, 4, 1]
+    ref = np.array(_scalar_forward(cfg, w, seq))
+    tok, par = np.array(seq), np.arange(-1, 3)
+    empty = np.zeros((2, 0, 2, 4))
+    got = oracle.verify_tree(cfg, w, empty, empty, tok, par)["logits"]
+    np.testing.assert_allclose(got, ref, atol=1e-11)
+
+
+def test_round_bf16_matches_torch():
+    x = np.random.default_rng(14).standard_normal(10000) * 3
+    x = np.concatenate([x, [1.00390625, 1.01171875, 0.0, -0.0]])   # exact ties: round to even
+    ref = torch.from_numpy(x).float().to(torch.bfloat16).double().numpy()
+    assert np.array_equal(oracle.round_bf16(x), ref)
