@@ -1,0 +1,195 @@
+/*
+ * specexec_mi.h -- C ABI of the MI355X (gfx950) SpecExec verification hot path.
+ *
+ * The three main calls follow the paper's problem statement:
+ *   sx_verify_tree  = FORWARD(tau, theta_target) of Alg. 1 (function PRECOMPUTE): one target
+ *                     forward over the K tree tokens under the merged tree mask of App. D,
+ *                     giving the K x vocab matrix "next_probs" (as logits, pre-softmax);
+ *   sx_accept_walk  = the loop body of Alg. 1: sample from the cached row of the current
+ *                     node, follow the child that carries the sampled token, stop on a miss;
+ *   sx_expand_topk  = the selectBest step of Alg. 2 with the nll score of its last lines
+ *                     (cumulative log-probability of parent plus log-probability of child,
+ *                     App. A Eq. 4-5).
+ * A few building blocks (GEMM, tree attention, row top-k) are exported as well so that they
+ * can be tested and profiled one by one.
+ *
+ * General rules
+ *   - Every pointer named "device" is GPU global memory owned by the caller; the library
+ *     never allocates, frees or keeps a pointer after the call returns.  Scratch memory is
+ *     passed in as `workspace`, sized by the matching *_workspace() query, 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; nothing synchronises with the host.  Outputs are valid once the
+ *     caller has synchronised the stream.
+ *   - Return value: SX_OK or a negative sx_status.  Errors that can be seen from the host
+ *     (null pointers, bad shapes, short workspace) are returned before anything is
+ *     launched.  Errors that live in device data (a parent index out of order, a token id
+ *     outside the vocabulary) are recorded by the kernels in the first word of the
+ *     workspace; sx_check_status() reads it back (this one call does synchronise).  After
+ *     such an error the outputs are unspecified, but no kernel reads or writes out of
+ *     bounds because of it.
+ *   - Nothing throws or aborts across this boundary.
+ */
+#ifndef SPECEXEC_MI_H
+#define SPECEXEC_MI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sx_status {
+  SX_OK = 0,
+  SX_ERR_NULL = -1,       /* a required pointer is NULL */
+  SX_ERR_SHAPE = -2,      /* a size is out of the supported range (see each call) */
+  SX_ERR_WORKSPACE = -3,  /* workspace missing, misaligned or smaller than the query says */
+  SX_ERR_DTYPE = -4,      /* cfg.dtype is neither SX_F32 nor SX_BF16 */
+  SX_ERR_HIP = -5,        /* a HIP call or kernel launch failed */
+  SX_ERR_TREE = -6        /* device data: parent_idx not in {-1} U [0,i), or token outside [0,V) */
+} sx_status;
+
+typedef enum sx_dtype { SX_F32 = 0, SX_BF16 = 1 } sx_dtype;
+
+/* Llama-style decoder shape.  Linear layers have no bias; embed and lm_head are untied. */
+typedef struct sx_model_cfg {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_base; /* 10000 for Llama-2 */
+  float rms_eps;   /* 1e-5 */
+  int32_t dtype;   /* sx_dtype of weights, prefix KV and tree KV */
+} sx_model_cfg;
+
+/* One decoder layer, device pointers, model dtype, row-major [out][in] (y = x W^T). */
+typedef struct sx_layer_weights {
+  const void *attn_norm; /* [d] */
+  const void *wq;        /* [Hq*Dh][d] */
+  const void *wk;        /* [Hkv*Dh][d] */
+  const void *wv;        /* [Hkv*Dh][d] */
+  const void *wo;        /* [d][Hq*Dh] */
+  const void *ffn_norm;  /* [d] */
+  const void *w_gate;    /* [F][d] */
+  const void *w_up;      /* [F][d] */
+  const void *w_down;    /* [d][F] */
+} sx_layer_weights;
+
+typedef struct sx_weights {
+  sx_model_cfg cfg;
+  const void *embed;              /* device [V][d] */
+  const sx_layer_weights *layers; /* HOST array of n_layers structs holding device pointers */
+  const void *final_norm;         /* device [d] */
+  const void *lm_head;            /* device [V][d] */
+} sx_weights;
+
+/* ------------------------------------------------------------------------------------------
+ * sx_verify_tree -- Alg. 1, PRECOMPUTE: next_probs := FORWARD(tau, theta_target); App. D:
+ * all tree tokens in one pass under a merged attention mask.
+ *
+ * Node i (0 <= i < T) carries token tree_tokens[i] and hangs under node parent_idx[i]
+ * (-1: directly under the last cached prefix token).  Nodes are in topological order,
+ * parent_idx[i] < i.  Node i sits at position P + depth(i) for the rotary embedding and
+ * attends to all P prefix keys, its tree ancestors and itself.  Query head h reads KV head
+ * h / (n_q_heads / n_kv_heads); scores are scaled by 1/sqrt(head_dim).
+ *
+ *   prefix_k, prefix_v  device [L][P][Hkv][Dh], model dtype; K already rotated at 0..P-1.
+ *                       May be NULL when P == 0.
+ *   tree_tokens, parent_idx   device int32 [T]
+ *   logits_out          device float [T][V]; row i = logits of the token after node i
+ *   tree_k_out, tree_v_out    device [L][T][Hkv][Dh], model dtype: the tree's own (rotated) K
+ *                       and V, for a later KV commit.  Both NULL = not wanted.
+ *
+ * Supported shapes.  SX_F32: head_dim even and <= 256, P + 2T <= 15360 (the scores of one node live in LDS).  SX_BF16: head_dim
+ * == 128, n_q_heads/n_kv_heads in {1,2,4,8}, d_model, Hq*Dh and d_ffn multiples of 64.
+ * T >= 1, P >= 0, T <= 16384.  In SX_BF16 the tensors a bf16 model materialises (normed
+ * activations, q, k, v, attention output, SwiGLU output) are rounded to bf16; the residual
+ * stream, softmax and norm statistics, and all accumulation are fp32.
+ * ---------------------------------------------------------------------------------------- */
+size_t sx_verify_tree_workspace(const sx_model_cfg *cfg, int32_t P, int32_t T);
+int sx_verify_tree(const sx_weights *w, const void *prefix_k, const void *prefix_v, int32_t P,
+                   const int32_t *tree_tokens, const int32_t *parent_idx, int32_t T,
+                   float *logits_out, void *tree_k_out, void *tree_v_out, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sx_accept_walk -- Alg. 1, main loop: p_target := cache[x]; x_next ~ sample(p_target).
+ *
+ * Starts at node 0 (which must be the only root), and repeats: draw a token from
+ * warp(softmax(logits[cur] / temperature), top_p) with the uniform u(seed, pos0 +
+ * depth(cur) + 1); emit it; move to the lowest-index child of cur that carries it; stop
+ * when there is none.  temperature == 0 means greedy (lowest-id argmax).  The nucleus is
+ * the shortest prefix, in (probability descending, id ascending) order, whose mass reaches
+ * top_p; the draw is the inverse CDF over the nucleus in id order at u * mass(nucleus).
+ * u(seed, pos) = top 24 bits of SplitMix64's mixer applied to seed + (pos+1)*0x9E3779B97F4A7C15.
+ * pos0 is the absolute position of node 0 (= P), so the stream of uniforms is the one
+ * sequential decoding would use (Sect. 4.1, seed-exact equivalence).
+ *
+ *   logits        device float [T][V]
+ *   draft_probs   ignored (may be NULL): SpecExec accepts with the target probability alone;
+ *                 only a SpecInfer-style ratio test would read it.
+ *   path_out      device int32 [T]: visited nodes, path_out[0] == 0
+ *   tokens_out    device int32 [T]: tokens_out[s] = token sampled at path_out[s]
+ *   n_out         device int32 [1]: number of entries written to both (>= 1); the number of
+ *                 accepted draft tokens is n_out - 1, the last token is the one that left the tree
+ * Supported: 1 <= V <= 131072, T >= 1, 0 < top_p <= 1, temperature >= 0.
+ * ---------------------------------------------------------------------------------------- */
+size_t sx_accept_walk_workspace(int32_t T, int32_t V);
+int sx_accept_walk(const float *logits, const float *draft_probs, const int32_t *tree_tokens,
+                   const int32_t *parent_idx, int32_t T, int32_t V, float temperature, float top_p,
+                   uint64_t seed, int32_t pos0, int32_t *path_out, int32_t *tokens_out,
+                   int32_t *n_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sx_expand_topk -- Alg. 2: topk := selectBest(batch, probs, tau, K), scored by
+ * nll := -log p_prefix - log p_i.
+ *
+ * For each of N expanded nodes: log-softmax of its V draft logits and its k best tokens
+ * (value descending, token id ascending on ties).  Then the B best of the N*k candidates by
+ * cum_logp[row] + logp (fp32), ties to the lower flat index row*k + rank.  Outputs are in
+ * that order.
+ *
+ *   logits     device float [N][V];  cum_logp  device float [N]
+ *   out_row, out_token   device int32 [B];  out_cum_logp  device float [B]
+ *   n_out      device int32 [1] = min(B, N*k)
+ * Supported: 1 <= k <= min(V, 256), V <= 131072, 1 <= B <= 8192, N >= 1, N*k < 2^31.
+ * ---------------------------------------------------------------------------------------- */
+size_t sx_expand_topk_workspace(int32_t N, int32_t V, int32_t k, int32_t B);
+int sx_expand_topk(const float *logits, const float *cum_logp, int32_t N, int32_t V, int32_t k,
+                   int32_t B, int32_t *out_row, int32_t *out_token, float *out_cum_logp,
+                   int32_t *n_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Reads the device-side status word of a workspace used by one of the calls above.
+ * Synchronises `stream`.  Returns SX_OK, SX_ERR_TREE, or SX_ERR_HIP. */
+int sx_check_status(const void *workspace, void *stream);
+
+const char *sx_status_string(int status);
+int sx_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Building blocks (the kernels the three calls are made of), exported for tests/profiling.
+ * ---------------------------------------------------------------------------------------- */
+
+/* First half of sx_expand_topk (Alg. 2, probs -> per-row best tokens): row-wise
+ * log-softmax + top-k.  topk_logp device float [N][k], topk_idx device int32 [N][k]. */
+int sx_row_logsoftmax_topk(const float *logits, int32_t N, int32_t V, int32_t k,
+                           float *topk_logp, int32_t *topk_idx, void *stream);
+
+/* Y = X W^T with bf16 operands and fp32 accumulation on the matrix cores; the linear layers
+ * of the decoder forward (Alg. 1, FORWARD).  X device bf16 [M][K] row-major, W device bf16
+ * [N][K] row-major, K % 64 == 0.  mode 0: Y float [M][N] = acc;  mode 1: Y float [M][N] += acc
+ * (residual add);  mode 2: W2 is a second [N][K] matrix and Y bf16 [M][N] =
+ * bf16(silu(X W^T) * (X W2^T)) (SwiGLU).  W2 is ignored in modes 0 and 1. */
+int sx_gemm_bf16(const void *X, const void *W, const void *W2, void *Y, int32_t M, int32_t N,
+                 int32_t K, int32_t mode, void *stream);
+
+/* Tree attention alone (App. D merged mask), bf16: q device bf16 [T][Hq][128], tree K/V
+ * [T][Hkv][128], prefix K/V [P][Hkv][128], out device bf16 [T][Hq][128]; n_q_heads/n_kv_heads in {1,2,4,8}.  workspace sized by
+ * sx_tree_attention_workspace. */
+size_t sx_tree_attention_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads);
+int sx_tree_attention_bf16(const void *q, const void *k_tree, const void *v_tree,
+                           const void *k_prefix, const void *v_prefix, const int32_t *parent_idx,
+                           int32_t T, int32_t P, int32_t n_q_heads, int32_t n_kv_heads, void *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECEXEC_MI_H */

@@ -1,0 +1,225 @@
+"""ctypes binding with the same names as the C ABI (include/specexec_mi.h): argument marshalling
+only.  torch provides device memory and the stream; every step of the path runs in the HIP library."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
+EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_accept_walk_workspace", "sx_accept_walk",
+           "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
+           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16"]
+
+SX_F32, SX_BF16 = 0, 1
+
+
+class SxError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+_LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+class _Layer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("cfg", _Cfg), ("embed", C.c_void_p), ("layers", C.POINTER(_Layer)), ("final_norm", C.c_void_p),
+                ("lm_head", C.c_void_p)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+                          "or python paper_2406_02532_amd/build.py). There is no fallback path.")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, f32, u64, sz = C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_size_t
+    L.sx_verify_tree_workspace.restype = sz
+    L.sx_verify_tree_workspace.argtypes = [C.POINTER(_Cfg), i32, i32]
+    L.sx_verify_tree.restype = C.c_int
+    L.sx_verify_tree.argtypes = [C.POINTER(_Weights), vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.sx_accept_walk_workspace.restype = sz
+    L.sx_accept_walk_workspace.argtypes = [i32, i32]
+    L.sx_accept_walk.restype = C.c_int
+    L.sx_accept_walk.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
+    L.sx_expand_topk_workspace.restype = sz
+    L.sx_expand_topk_workspace.argtypes = [i32, i32, i32, i32]
+    L.sx_expand_topk.restype = C.c_int
+    L.sx_expand_topk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.sx_check_status.restype = C.c_int
+    L.sx_check_status.argtypes = [vp, vp]
+    L.sx_status_string.restype = C.c_char_p
+    L.sx_status_string.argtypes = [C.c_int]
+    L.sx_version.restype = C.c_int
+    L.sx_row_logsoftmax_topk.restype = C.c_int
+    L.sx_row_logsoftmax_topk.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    L.sx_gemm_bf16.restype = C.c_int
+    L.sx_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.sx_tree_attention_workspace.restype = sz
+    L.sx_tree_attention_workspace.argtypes = [i32, i32, i32]
+    L.sx_tree_attention_bf16.restype = C.c_int
+    L.sx_tree_attention_bf16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    return L
+
+
+lib = _load()
+
+
+def status_string(code: int) -> str:
+    return lib.sx_status_string(int(code)).decode()
+
+
+def version() -> int:
+    return lib.sx_version()
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise SxError(rc, where)
+
+
+def _workspace(nbytes: int, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)  # torch allocations are 512-B aligned
+
+
+def _make_cfg(cfg) -> _Cfg:
+    return _Cfg(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab,
+                cfg.rope_base, cfg.rms_eps, SX_BF16 if cfg.dtype == "bf16" else SX_F32)
+
+
+class ModelWeights:
+    """sx_weights built from a dict of device tensors (embed, layers[list of dict], final_norm, lm_head).
+    Holds references to the tensors so the pointers stay valid."""
+
+    def __init__(self, cfg, w: dict):
+        self.cfg = cfg
+        self._keep = w
+        self._layers = (_Layer * cfg.n_layers)()
+        for l, lw in enumerate(w["layers"]):
+            for n in _LAYER_FIELDS:
+                t = lw[n]
+                assert t.is_contiguous() and t.dtype == cfg.torch_dtype
+                setattr(self._layers[l], n, t.data_ptr())
+        self.c = _Weights(_make_cfg(cfg), w["embed"].data_ptr(), self._layers, w["final_norm"].data_ptr(),
+                          w["lm_head"].data_ptr())
+        self.device = w["embed"].device
+
+
+def verify_tree_workspace(cfg, P: int, T: int) -> int:
+    c = _make_cfg(cfg)
+    return lib.sx_verify_tree_workspace(C.byref(c), P, T)
+
+
+def verify_tree(weights: ModelWeights, prefix_k, prefix_v, tree_tokens, parent_idx, logits_out=None,
+                tree_k_out=None, tree_v_out=None, workspace=None, stream=None):
+    """sx_verify_tree.  Returns (logits_out, workspace); allocates them with torch when not given."""
+    cfg = weights.cfg
+    T = int(tree_tokens.numel())
+    P = 0 if prefix_k is None else int(prefix_k.shape[1])
+    if logits_out is None:
+        logits_out = torch.empty((T, cfg.vocab), dtype=torch.float32, device=weights.device)
+    if workspace is None:
+        workspace = _workspace(verify_tree_workspace(cfg, P, T), weights.device)
+    rc = lib.sx_verify_tree(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), P, _ptr(tree_tokens), _ptr(parent_idx), T,
+                            _ptr(logits_out), _ptr(tree_k_out), _ptr(tree_v_out), _ptr(workspace), workspace.numel(),
+                            _stream(stream))
+    _check(rc, "sx_verify_tree")
+    return logits_out, workspace
+
+
+def accept_walk(logits, tree_tokens, parent_idx, temperature: float, top_p: float, seed: int, pos0: int,
+                path_out=None, tokens_out=None, n_out=None, workspace=None, stream=None, draft_probs=None):
+    """sx_accept_walk.  Returns (path_out, tokens_out, n_out, workspace) -- device tensors."""
+    T, V = logits.shape
+    dev = logits.device
+    if path_out is None:
+        path_out = torch.empty(T, dtype=torch.int32, device=dev)
+    if tokens_out is None:
+        tokens_out = torch.empty(T, dtype=torch.int32, device=dev)
+    if n_out is None:
+        n_out = torch.empty(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.sx_accept_walk_workspace(T, V), dev)
+    rc = lib.sx_accept_walk(_ptr(logits), _ptr(draft_probs), _ptr(tree_tokens), _ptr(parent_idx), T, V, temperature, top_p,
+                            seed, pos0, _ptr(path_out), _ptr(tokens_out), _ptr(n_out), _ptr(workspace), workspace.numel(),
+                            _stream(stream))
+    _check(rc, "sx_accept_walk")
+    return path_out, tokens_out, n_out, workspace
+
+
+def expand_topk(logits, cum_logp, k: int, B: int, out_row=None, out_token=None, out_cum_logp=None, n_out=None,
+                workspace=None, stream=None):
+    """sx_expand_topk.  Returns (out_row, out_token, out_cum_logp, n_out, workspace)."""
+    N, V = logits.shape
+    dev = logits.device
+    if out_row is None:
+        out_row = torch.empty(B, dtype=torch.int32, device=dev)
+    if out_token is None:
+        out_token = torch.empty(B, dtype=torch.int32, device=dev)
+    if out_cum_logp is None:
+        out_cum_logp = torch.empty(B, dtype=torch.float32, device=dev)
+    if n_out is None:
+        n_out = torch.empty(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.sx_expand_topk_workspace(N, V, k, B), dev)
+    rc = lib.sx_expand_topk(_ptr(logits), _ptr(cum_logp), N, V, k, B, _ptr(out_row), _ptr(out_token), _ptr(out_cum_logp),
+                            _ptr(n_out), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "sx_expand_topk")
+    return out_row, out_token, out_cum_logp, n_out, workspace
+
+
+def row_logsoftmax_topk(logits, k: int, topk_logp=None, topk_idx=None, stream=None):
+    N, V = logits.shape
+    if topk_logp is None:
+        topk_logp = torch.empty((N, k), dtype=torch.float32, device=logits.device)
+    if topk_idx is None:
+        topk_idx = torch.empty((N, k), dtype=torch.int32, device=logits.device)
+    _check(lib.sx_row_logsoftmax_topk(_ptr(logits), N, V, k, _ptr(topk_logp), _ptr(topk_idx), _stream(stream)),
+           "sx_row_logsoftmax_topk")
+    return topk_logp, topk_idx
+
+
+def gemm_bf16(X, W, Y, mode: int = 0, W2=None, stream=None):
+    """sx_gemm_bf16: Y = X W^T (mode 0), Y += X W^T (mode 1), Y = bf16(silu(X W^T) * (X W2^T)) (mode 2)."""
+    M, K = X.shape
+    N = W.shape[0]
+    _check(lib.sx_gemm_bf16(_ptr(X), _ptr(W), _ptr(W2), _ptr(Y), M, N, K, mode, _stream(stream)), "sx_gemm_bf16")
+    return Y
+
+
+def tree_attention_bf16(q, k_tree, v_tree, k_prefix, v_prefix, parent_idx, out=None, workspace=None, stream=None):
+    T, Hq, Dh = q.shape
+    Hkv = k_tree.shape[1]
+    P = 0 if k_prefix is None else int(k_prefix.shape[0])
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = _workspace(lib.sx_tree_attention_workspace(T, Hq, Hkv), q.device)
+    _check(lib.sx_tree_attention_bf16(_ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(k_prefix), _ptr(v_prefix), _ptr(parent_idx),
+                                      T, P, Hq, Hkv, _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "sx_tree_attention_bf16")
+    return out, workspace
+
+
+def check_status(workspace, stream=None) -> int:
+    return lib.sx_check_status(_ptr(workspace), _stream(stream))

@@ -1,0 +1,128 @@
+// The small memory-bound pieces of the decoder forward (Alg. 1, FORWARD): embedding gather,
+// RMSNorm, rotary embedding at position P + tree depth, SwiGLU (fp32 path only; the bf16 path
+// fuses it into the gate/up GEMM).
+#include "kernels.h"
+
+namespace {
+
+template <typename T>
+__device__ __forceinline__ float ld(const T* p, size_t i);
+template <>
+__device__ __forceinline__ float ld<float>(const float* p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float ld<unsigned short>(const unsigned short* p, size_t i) {
+  return bf16_bits_to_f32(p[i]);
+}
+template <typename T>
+__device__ __forceinline__ void st(T* p, size_t i, float v);
+template <>
+__device__ __forceinline__ void st<float>(float* p, size_t i, float v) { p[i] = v; }
+template <>
+__device__ __forceinline__ void st<unsigned short>(unsigned short* p, size_t i, float v) {
+  p[i] = (unsigned short)f32_to_bf16_bits(v);
+}
+
+template <typename W>
+__global__ void embed_kernel(const W* __restrict__ embed, const int* __restrict__ tok, int d, float* __restrict__ h) {
+  const int i = blockIdx.x;
+  const size_t src = (size_t)tok[i] * d, dst = (size_t)i * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) h[dst + c] = ld<W>(embed, src + c);
+}
+
+// One workgroup (256 lanes) per row: x = h * rsqrt(mean(h^2) + eps) * g.
+template <typename W>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const W* __restrict__ g, int d,
+                                                      float eps, W* __restrict__ x) {
+  __shared__ float red[4];
+  const size_t row = (size_t)blockIdx.x * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float v = h[row + c];
+    ss += v * v;
+  }
+  ss = block_sum<4>(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += 256) st<W>(x, row + c, h[row + c] * r * ld<W>(g, c));
+}
+
+// Pair (j, j + Dh/2) of every q and k head is rotated by the node's angle; v is copied.
+template <typename W>
+__global__ void rope_split_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs, int T, int Hq, int Hkv,
+                                  int Dh, W* __restrict__ q, W* __restrict__ k, W* __restrict__ v) {
+  const int half = Dh / 2;
+  const int heads = Hq + 2 * Hkv;
+  const size_t total = (size_t)T * heads * half;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int j = (int)(idx % half);
+  const int hd = (int)((idx / half) % heads);
+  const int i = (int)(idx / ((size_t)half * heads));
+  const float* src = qkv + ((size_t)i * heads + hd) * Dh;
+  const float a = src[j], b = src[j + half];
+  if (hd < Hq + Hkv) {
+    const float2 t = cs[(size_t)i * half + j];
+    const float ra = a * t.x - b * t.y, rb = a * t.y + b * t.x;
+    if (hd < Hq) {
+      const size_t o = ((size_t)i * Hq + hd) * Dh;
+      st<W>(q, o + j, ra);
+      st<W>(q, o + j + half, rb);
+    } else {
+      const size_t o = ((size_t)i * Hkv + (hd - Hq)) * Dh;
+      st<W>(k, o + j, ra);
+      st<W>(k, o + j + half, rb);
+    }
+  } else {
+    const size_t o = ((size_t)i * Hkv + (hd - Hq - Hkv)) * Dh;
+    st<W>(v, o + j, a);
+    st<W>(v, o + j + half, b);
+  }
+}
+
+__global__ void swiglu_f32_kernel(const float* __restrict__ g, const float* __restrict__ u, float* __restrict__ a,
+                                  size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const float x = g[i];
+    a[i] = x / (1.0f + expf(-x)) * u[i];
+  }
+}
+
+}  // namespace
+
+int sx_launch_embed(const void* embed, int dtype, const int32_t* tok_s, int T, int d, float* h, hipStream_t s) {
+  if (dtype == SX_F32)
+    embed_kernel<float><<<T, 256, 0, s>>>((const float*)embed, tok_s, d, h);
+  else
+    embed_kernel<unsigned short><<<T, 256, 0, s>>>((const unsigned short*)embed, tok_s, d, h);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_rmsnorm(const float* h, const void* gain, int dtype, int T, int d, float eps, void* x_out,
+                      hipStream_t s) {
+  if (dtype == SX_F32)
+    rmsnorm_kernel<float><<<T, 256, 0, s>>>(h, (const float*)gain, d, eps, (float*)x_out);
+  else
+    rmsnorm_kernel<unsigned short><<<T, 256, 0, s>>>(h, (const unsigned short*)gain, d, eps, (unsigned short*)x_out);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_rope_split(const float* qkv, const float2* rope_cs, int T, int Hq, int Hkv, int Dh, int dtype, void* q,
+                         void* k, void* v, hipStream_t s) {
+  const size_t total = (size_t)T * (Hq + 2 * Hkv) * (Dh / 2);
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == SX_F32)
+    rope_split_kernel<float><<<blocks, 256, 0, s>>>(qkv, rope_cs, T, Hq, Hkv, Dh, (float*)q, (float*)k, (float*)v);
+  else
+    rope_split_kernel<unsigned short><<<blocks, 256, 0, s>>>(qkv, rope_cs, T, Hq, Hkv, Dh, (unsigned short*)q,
+                                                             (unsigned short*)k, (unsigned short*)v);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_swiglu_f32(const float* g, const float* u, float* a, size_t n, hipStream_t s) {
+  swiglu_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(g, u, a, n);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}

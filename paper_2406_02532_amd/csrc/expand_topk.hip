@@ -1,0 +1,373 @@
+// Draft-side expansion step (Alg. 2: probs -> selectBest by cumulative log-probability).
+//
+// Kernel 1, row_topk_kernel: one workgroup per expanded node.  The row of V fp32 logits is read
+// from HBM exactly once into registers (float4 per lane, fully coalesced), and everything else
+// -- max, sum of exponentials, the k best entries -- is computed from those registers.  This is
+// the HBM-bound part: 4*V bytes per row in, 8*k bytes out.
+// Selection: the k-th largest of the per-thread maxima is a lower bound t0 of the k-th largest
+// entry of the row (k distinct threads hold a value >= t0), so only entries >= t0 can be among
+// the k best.  For k << V that leaves a few dozen candidates, which are sorted in LDS by
+// (value descending, index ascending).  Rows where the bound is useless (massive ties) fall back
+// to an exact bitwise threshold search over the same registers.
+//
+// Kernel 2, global_select_kernel: one workgroup picks the B best of the N*k candidates by
+// score = cum_logp[row] + logp, ties to the lower flat index, and writes them in that order.
+#include "common.h"
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kCandCap = 1024;  // LDS slots for row candidates before the exact fallback is taken
+
+template <int THREADS>
+__device__ __forceinline__ int block_count(bool pred, int* red) {
+  return block_sum_i<THREADS / 64>(pred ? 1 : 0, red);
+}
+
+// Exact selection for rows the cheap bound cannot handle.  Bitwise search for the k-th largest
+// order key, then for the index below which ties are taken, each probe being one pass over the
+// row (served by L2: the row was just read).  Leaves exactly k entries in cand[], returns k.
+template <int THREADS>
+__device__ __noinline__ int exact_topk_from_memory(const float* __restrict__ x, int V, int k, int* redi, int* s_cnt,
+                                                   unsigned long long* cand) {
+  constexpr int NW = THREADS / 64;
+  const int tid = threadIdx.x;
+  unsigned K = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const unsigned trial = K | (1u << bit);
+    int c = 0;
+    for (int i = tid; i < V; i += THREADS) c += (f32_order_key(x[i]) >= trial) ? 1 : 0;
+    if (block_sum_i<NW>(c, redi) >= k) K = trial;
+  }
+  int cg = 0;
+  for (int i = tid; i < V; i += THREADS) cg += (f32_order_key(x[i]) > K) ? 1 : 0;
+  const int need = k - block_sum_i<NW>(cg, redi);  // ties to take, >= 1
+  unsigned Y = 0;                                 // largest Y with #(tie, idx < Y) <= need
+  for (int bit = 17; bit >= 0; --bit) {
+    const unsigned trial = Y | (1u << bit);
+    int c = 0;
+    for (int i = tid; i < V && (unsigned)i < trial; i += THREADS) c += (f32_order_key(x[i]) == K) ? 1 : 0;
+    if (block_sum_i<NW>(c, redi) <= need) Y = trial;
+  }
+  if (tid == 0) *s_cnt = 0;
+  __syncthreads();
+  for (int i = tid; i < V; i += THREADS) {
+    const unsigned key = f32_order_key(x[i]);
+    if (key > K || (key == K && (unsigned)i < Y)) {
+      const int pos = atomicAdd(s_cnt, 1);
+      if (pos < kCandCap) cand[pos] = ((unsigned long long)(~key) << 32) | (unsigned)i;
+    }
+  }
+  __syncthreads();
+  const int C = min(*s_cnt, kCandCap);
+  __syncthreads();
+  return C;
+}
+
+// THREADS lanes, each holding IPT4 float4 of the row.  Element (j, c) of a lane is index
+// (j*THREADS + tid)*4 + c.
+template <int THREADS, int IPT4, bool VEC>
+__global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restrict__ logits,
+                                                           const float* __restrict__ cum_logp, int V, int k,
+                                                           float* __restrict__ topk_logp,
+                                                           int* __restrict__ topk_idx,
+                                                           float* __restrict__ score) {
+  constexpr int NW = THREADS / 64;
+  __shared__ float smax[THREADS];
+  __shared__ float redf[16];
+  __shared__ int redi[16];
+  __shared__ float s_t0;
+  __shared__ int s_cnt;
+  __shared__ unsigned long long cand[kCandCap];
+
+  const int tid = threadIdx.x;
+  const size_t row = blockIdx.x;
+  const float* x = logits + row * (size_t)V;
+  const float NEG_INF = -__builtin_huge_valf();
+
+  float v[IPT4 * 4];
+#pragma unroll
+  for (int j = 0; j < IPT4; ++j) {
+    const int base = (j * THREADS + tid) * 4;
+    if (VEC) {
+      if (base < V) {
+        const float4 t = *reinterpret_cast<const float4*>(x + base);
+        v[4 * j + 0] = t.x; v[4 * j + 1] = t.y; v[4 * j + 2] = t.z; v[4 * j + 3] = t.w;
+      } else {
+        v[4 * j + 0] = v[4 * j + 1] = v[4 * j + 2] = v[4 * j + 3] = NEG_INF;
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[4 * j + c] = (base + c < V) ? x[base + c] : NEG_INF;
+    }
+  }
+
+  // ---- log-sum-exp ---------------------------------------------------------------------
+  float tm = NEG_INF;
+#pragma unroll
+  for (int e = 0; e < IPT4 * 4; ++e) tm = fmaxf(tm, v[e]);
+  smax[tid] = tm;
+  if (tid == 0) s_cnt = 0;
+  const float M = block_max<NW>(tm, redf);
+  float se = 0.f;
+#pragma unroll
+  for (int e = 0; e < IPT4 * 4; ++e) se += __builtin_amdgcn_exp2f((v[e] - M) * kLog2e);
+  const float S = block_sum<NW>(se, redf);
+  const float lse = M + logf(S);
+
+  // ---- lower bound t0 = k-th largest of a set of group maxima (rank by value, then group id) -----
+  // k <= 64: the lanes are folded into 64 groups and one wave ranks them with lane broadcasts
+  // (hardly looser than per-lane maxima, and ~THREADS/64 times cheaper); else every lane is a group.
+  if (k <= 64) {
+    if (tid < 64) {
+      constexpr int GS = THREADS / 64;
+      float gm = smax[tid * GS];
+#pragma unroll
+      for (int j = 1; j < GS; ++j) gm = fmaxf(gm, smax[tid * GS + j]);
+      int rank = 0;
+#pragma unroll
+      for (int j = 0; j < 64; ++j) {
+        const float o = __shfl(gm, j, 64);
+        rank += (o > gm || (o == gm && j < tid)) ? 1 : 0;
+      }
+      if (rank == k - 1) s_t0 = gm;
+    }
+  } else {
+    int rank = 0;
+    for (int j = 0; j < THREADS; ++j) {
+      const float o = smax[j];
+      rank += (o > tm || (o == tm && j < tid)) ? 1 : 0;
+    }
+    if (rank == k - 1) s_t0 = tm;
+  }
+  __syncthreads();
+  const float t0 = s_t0;
+
+  // ---- gather candidates >= t0 ---------------------------------------------------------------
+#pragma unroll
+  for (int j = 0; j < IPT4; ++j) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int idx = (j * THREADS + tid) * 4 + c;
+      if (idx < V && v[4 * j + c] >= t0) {
+        const int pos = atomicAdd(&s_cnt, 1);
+        if (pos < kCandCap)
+          cand[pos] = ((unsigned long long)(~f32_order_key(v[4 * j + c])) << 32) | (unsigned)idx;
+      }
+    }
+  }
+  __syncthreads();
+  int C = s_cnt;
+  __syncthreads();
+
+  if (C > kCandCap) {  // the bound was useless (massive ties): exact search, re-reading the row from L2
+    C = exact_topk_from_memory<THREADS>(x, V, k, redi, &s_cnt, cand);
+  }
+
+  // ---- order the candidates and emit the first k -------------------------------------------------
+  const int n = next_pow2(C < 2 ? 2 : C);
+  for (int i = C + tid; i < n; i += THREADS) cand[i] = ~0ull;
+  block_bitonic_sort_u64<THREADS>(cand, n);
+  const float cl = cum_logp ? cum_logp[row] : 0.f;
+  for (int c = tid; c < k; c += THREADS) {
+    const unsigned long long e = cand[c];
+    const float val = f32_from_order_key(~(unsigned)(e >> 32));
+    const float lp = val - lse;
+    const size_t o = row * (size_t)k + c;
+    topk_idx[o] = (int)(unsigned)(e & 0xFFFFFFFFull);
+    topk_logp[o] = lp;
+    if (score) score[o] = cl + lp;
+  }
+}
+
+// One workgroup of 512 lanes; lane t owns the flat candidates [t*per, (t+1)*per).
+// REG = true keeps the (<= 128) keys of a lane in registers.
+constexpr int kSelThreads = 512;
+
+template <bool REG>
+__global__ __launch_bounds__(kSelThreads) void global_select_kernel(const float* __restrict__ score,
+                                                                    const int* __restrict__ topk_idx, int n, int k,
+                                                                    int B, int per, int* __restrict__ out_row,
+                                                                    int* __restrict__ out_token,
+                                                                    float* __restrict__ out_score,
+                                                                    int* __restrict__ n_out) {
+  constexpr int NW = kSelThreads / 64;
+  constexpr int RK = 128;  // keys a lane can hold in registers
+  extern __shared__ unsigned long long sbuf[];
+  __shared__ int redi[16];
+  __shared__ int s_wave_ties[NW];
+  __shared__ int s_pos;
+
+  const int tid = threadIdx.x;
+  const int lo = tid * per;
+  const int hi = min(n, lo + per);
+  const int Bsel = min(B, n);
+  // Order keys; slots past the lane's range hold key 0, below every real key.
+  unsigned key[REG ? RK : 1];
+  if (REG) {
+#pragma unroll
+    for (int e = 0; e < RK; ++e) key[e] = (lo + e < hi) ? f32_order_key(score[lo + e]) : 0u;
+  }
+
+  unsigned K = 0;  // largest key with #(key >= K) >= Bsel
+  if (n > Bsel) {
+    for (int bit = 31; bit >= 0; --bit) {
+      const unsigned trial = K | (1u << bit);
+      int c = 0;
+      if (REG) {
+#pragma unroll
+        for (int e = 0; e < RK; ++e) c += (key[e] >= trial) ? 1 : 0;
+      } else {
+        for (int i = lo; i < hi; ++i) c += (f32_order_key(score[i]) >= trial) ? 1 : 0;
+      }
+      if (block_sum_i<NW>(c, redi) >= Bsel) K = trial;
+    }
+  }
+  // ties: the `need` lowest flat indices among keys == K
+  int gt = 0, eq = 0;
+  if (REG) {
+#pragma unroll
+    for (int e = 0; e < RK; ++e) {
+      gt += (key[e] > K) ? 1 : 0;
+      eq += (key[e] == K) ? 1 : 0;
+    }
+  } else {
+    for (int i = lo; i < hi; ++i) {
+      const unsigned kk = f32_order_key(score[i]);
+      gt += kk > K;
+      eq += kk == K;
+    }
+  }
+  const int need = Bsel - block_sum_i<NW>(gt, redi);
+  int incl = eq;  // inclusive prefix of `eq` over lanes = flat-index order
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o, 64);
+    if ((tid & 63) >= o) incl += t;
+  }
+  if ((tid & 63) == 63) s_wave_ties[tid >> 6] = incl;
+  if (tid == 0) s_pos = 0;
+  __syncthreads();
+  int tie_rank = incl - eq;
+  for (int w = 0; w < (tid >> 6); ++w) tie_rank += s_wave_ties[w];
+
+  auto push = [&](unsigned kk, int flat) {
+    const int pos = atomicAdd(&s_pos, 1);
+    sbuf[pos] = ((unsigned long long)(~kk) << 32) | (unsigned)flat;
+  };
+  if (REG) {
+#pragma unroll
+    for (int e = 0; e < RK; ++e)
+      if (key[e] > K) push(key[e], lo + e);
+  } else {
+    for (int i = lo; i < hi; ++i) {
+      const unsigned kk = f32_order_key(score[i]);
+      if (kk > K) push(kk, i);
+    }
+  }
+  if (eq > 0 && tie_rank < need) {  // rare: this lane owns some of the ties that make the cut
+    for (int i = lo; i < hi; ++i) {
+      const unsigned kk = f32_order_key(score[i]);
+      if (kk == K) {
+        if (tie_rank < need) push(kk, i);
+        ++tie_rank;
+      }
+    }
+  }
+  __syncthreads();
+  const int nsort = next_pow2(Bsel < 2 ? 2 : Bsel);
+  for (int i = Bsel + tid; i < nsort; i += kSelThreads) sbuf[i] = ~0ull;
+  block_bitonic_sort_u64<kSelThreads>(sbuf, nsort);
+  for (int i = tid; i < Bsel; i += kSelThreads) {
+    const unsigned flat = (unsigned)(sbuf[i] & 0xFFFFFFFFull);
+    out_row[i] = (int)(flat / (unsigned)k);
+    out_token[i] = topk_idx[flat];
+    out_score[i] = score[flat];
+  }
+  if (tid == 0) n_out[0] = Bsel;
+}
+
+template <int THREADS, int IPT4>
+void launch_row(const float* logits, const float* cum, int N, int V, int k, float* lp, int* idx, float* score,
+                hipStream_t st) {
+  const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(logits) & 15) == 0);
+  if (vec)
+    row_topk_kernel<THREADS, IPT4, true><<<N, THREADS, 0, st>>>(logits, cum, V, k, lp, idx, score);
+  else
+    row_topk_kernel<THREADS, IPT4, false><<<N, THREADS, 0, st>>>(logits, cum, V, k, lp, idx, score);
+}
+
+int row_topk_dispatch(const float* logits, const float* cum, int N, int V, int k, float* lp, int* idx, float* score,
+                      hipStream_t st) {
+  // lanes x float4-per-lane sized so that a row fits in registers with >= 2 workgroups per CU
+  if (V <= 1024) launch_row<256, 1>(logits, cum, N, V, k, lp, idx, score, st);
+  else if (V <= 4096) launch_row<256, 4>(logits, cum, N, V, k, lp, idx, score, st);
+  else if (V <= 16384) launch_row<256, 16>(logits, cum, N, V, k, lp, idx, score, st);
+  else if (V <= 32768) launch_row<512, 16>(logits, cum, N, V, k, lp, idx, score, st);
+  else if (V <= 65536) launch_row<1024, 16>(logits, cum, N, V, k, lp, idx, score, st);
+  else launch_row<1024, 32>(logits, cum, N, V, k, lp, idx, score, st);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+bool row_shape_ok(int N, int V, int k) {
+  return N >= 1 && V >= 1 && V <= 131072 && k >= 1 && k <= 256 && k <= V && (long long)N * k < (1ll << 31);
+}
+
+}  // namespace
+
+extern "C" int sx_row_logsoftmax_topk(const float* logits, int32_t N, int32_t V, int32_t k, float* topk_logp,
+                                      int32_t* topk_idx, void* stream) {
+  if (!logits || !topk_logp || !topk_idx) return SX_ERR_NULL;
+  if (!row_shape_ok(N, V, k)) return SX_ERR_SHAPE;
+  return row_topk_dispatch(logits, nullptr, N, V, k, topk_logp, topk_idx, nullptr, (hipStream_t)stream);
+}
+
+// workspace: header | score f32[N*k] | topk_logp f32[N*k] | topk_idx i32[N*k]
+extern "C" size_t sx_expand_topk_workspace(int32_t N, int32_t V, int32_t k, int32_t B) {
+  (void)V;
+  (void)B;
+  if (N < 1 || k < 1) return 0;
+  const size_t nk = sx_align_up((size_t)N * (size_t)k * 4, 256);
+  return SX_WS_HEADER + 3 * nk;
+}
+
+extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_t N, int32_t V, int32_t k, int32_t B,
+                              int32_t* out_row, int32_t* out_token, float* out_cum_logp, int32_t* n_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!logits || !cum_logp || !out_row || !out_token || !out_cum_logp || !n_out) return SX_ERR_NULL;
+  if (!row_shape_ok(N, V, k) || B < 1 || B > 8192) return SX_ERR_SHAPE;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) ||
+      workspace_bytes < sx_expand_topk_workspace(N, V, k, B))
+    return SX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t nk = sx_align_up((size_t)N * (size_t)k * 4, 256);
+  char* ws = static_cast<char*>(workspace);
+  float* score = reinterpret_cast<float*>(ws + SX_WS_HEADER);
+  float* lp = reinterpret_cast<float*>(ws + SX_WS_HEADER + nk);
+  int* idx = reinterpret_cast<int*>(ws + SX_WS_HEADER + 2 * nk);
+  const int rc = row_topk_dispatch(logits, cum_logp, N, V, k, lp, idx, score, st);
+  if (rc != SX_OK) return rc;
+  const int n = N * k;
+  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int Bsel = B < n ? B : n;
+  int nsort = 2;
+  while (nsort < Bsel) nsort <<= 1;
+  const size_t shmem = (size_t)nsort * sizeof(unsigned long long);
+  static bool configured = false;  // B = 8192 needs the full 64 KB of dynamic LDS next to the static arrays
+  if (!configured) {
+    SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
+    SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
+    configured = true;
+  }
+  if (per <= 128)
+    global_select_kernel<true><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
+                                                               out_cum_logp, n_out);
+  else
+    global_select_kernel<false><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
+                                                                out_cum_logp, n_out);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}

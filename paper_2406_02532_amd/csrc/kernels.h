@@ -1,0 +1,45 @@
+// Host-side launchers shared between the translation units of the library.  Each returns an
+// sx_status and only enqueues work on the given stream.
+#pragma once
+#include "common.h"
+
+// ---- tree bookkeeping (tree_prep.hip) -------------------------------------------------------------
+// Checks parent/token ranges (status word <- SX_ERR_TREE on violation), writes sanitised copies,
+// the depth of every node and the rotary table cs[T][Dh/2] = (cos, sin) of (P+depth)*base^(-2j/Dh).
+int sx_launch_tree_prep(const int32_t* tokens, const int32_t* parent, int T, int V, int P, int head_dim,
+                        float rope_base, int32_t* tok_s, int32_t* par_s, int32_t* depth, float2* rope_cs,
+                        int32_t* status, hipStream_t st);
+// Per query tile of `nodes_per_tile` consecutive nodes: the sorted union of their ancestors
+// (klist[tile][0..kcnt[tile])) and, per node, a bitmask over positions of that list
+// (rowmask[node][w], bit b of word w <=> list position 64w+b is an ancestor-or-self of node).
+int sx_launch_qtile_prep(const int32_t* par_s, int T, int nodes_per_tile, int32_t* klist, int32_t* kcnt,
+                         unsigned long long* rowmask, hipStream_t st);
+
+// ---- elementwise (elementwise.hip) -----------------------------------------------------------------
+int sx_launch_embed(const void* embed, int dtype, const int32_t* tok_s, int T, int d, float* h, hipStream_t st);
+int sx_launch_rmsnorm(const float* h, const void* gain, int dtype, int T, int d, float eps, void* x_out,
+                      hipStream_t st);
+// qkv fp32 [T][Nq+2Nkv] -> q (dtype) [T][Hq][Dh] rotated, k (dtype) [T][Hkv][Dh] rotated, v (dtype)
+int sx_launch_rope_split(const float* qkv, const float2* rope_cs, int T, int Hq, int Hkv, int Dh, int dtype,
+                         void* q, void* k, void* v, hipStream_t st);
+int sx_launch_swiglu_f32(const float* g, const float* u, float* a, size_t n, hipStream_t st);
+
+// ---- fp32 reference-precision path (path_f32.hip) ---------------------------------------------------
+// Y[M][N] (+)= X[M][K] W[N][K]^T, all fp32, ldy = row stride of Y.
+int sx_launch_gemm_f32(const float* X, const float* W, float* Y, int M, int N, int K, int ldy, bool accumulate,
+                       hipStream_t st);
+int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_tree, const float* k_prefix,
+                            const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int P, int Hq,
+                            int Hkv, int Dh, float* out, hipStream_t st);
+
+// ---- bf16 MFMA path -------------------------------------------------------------------------------
+enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2 };
+// Y = X [W0;W1;W2]^T with n0/n1/n2 rows per segment (modes 0/1, Y fp32 [M][n0+n1+n2]), or
+// Y bf16 [M][n0] = silu(X W0^T) * (X W1^T) (mode 2, n1 == n0, n2 == 0).
+int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
+                        void* Y, int M, int K, int mode, hipStream_t st);
+int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
+                             const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
+                             const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,
+                             hipStream_t st);
+static inline int sx_attn_nodes_per_tile(int Hq, int Hkv) { return 128 / (Hq / Hkv); }

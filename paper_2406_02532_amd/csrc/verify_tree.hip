@@ -1,0 +1,247 @@
+// sx_verify_tree: host-side orchestration of the target forward over a token tree (Alg. 1,
+// PRECOMPUTE: next_probs := FORWARD(tau, theta_target); App. D: one pass under the merged tree mask).
+// Everything is enqueued on the caller's stream; there is no host synchronisation and no allocation.
+#include <string.h>
+
+#include "kernels.h"
+
+namespace {
+
+// Hands out 256-byte aligned slices of the workspace; with a null base it only measures.
+struct Carver {
+  uintptr_t base;
+  size_t off;
+  explicit Carver(void* p) : base(reinterpret_cast<uintptr_t>(p)), off(SX_WS_HEADER) {}
+  template <typename T>
+  T* take(size_t n) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += sx_align_up(n * sizeof(T), 256);
+    return p;
+  }
+};
+
+struct Layout {
+  int32_t *tok_s, *par_s, *depth, *klist, *kcnt;
+  float2* rope_cs;
+  unsigned long long* rowmask;
+  float *h, *qkv, *gate, *up;
+  void *x, *q, *o, *act, *tk, *tv;
+  size_t bytes;
+};
+
+// One function lays the workspace out, for the size query (base == nullptr) and for the run.
+Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
+  (void)P;
+  Carver cv(ws);
+  Layout L;
+  const size_t es = c.dtype == SX_BF16 ? 2 : 4;
+  const size_t Nq = (size_t)c.n_q_heads * c.head_dim, Nkv = (size_t)c.n_kv_heads * c.head_dim;
+  L.tok_s = cv.take<int32_t>(T);
+  L.par_s = cv.take<int32_t>(T);
+  L.depth = cv.take<int32_t>(T);
+  L.rope_cs = cv.take<float2>((size_t)T * (c.head_dim / 2));
+  L.h = cv.take<float>((size_t)T * c.d_model);
+  L.x = cv.take<char>((size_t)T * c.d_model * es);
+  L.qkv = cv.take<float>((size_t)T * (Nq + 2 * Nkv));
+  L.q = cv.take<char>((size_t)T * Nq * es);
+  L.tk = cv.take<char>((size_t)T * Nkv * es);
+  L.tv = cv.take<char>((size_t)T * Nkv * es);
+  L.o = cv.take<char>((size_t)T * Nq * es);
+  L.act = cv.take<char>((size_t)T * c.d_ffn * es);
+  if (c.dtype == SX_BF16) {
+    const int npt = sx_attn_nodes_per_tile(c.n_q_heads, c.n_kv_heads);
+    const size_t tiles = (T + npt - 1) / npt;
+    L.klist = cv.take<int32_t>(tiles * (size_t)T);
+    L.kcnt = cv.take<int32_t>(tiles);
+    L.rowmask = cv.take<unsigned long long>((size_t)T * ((T + 63) / 64));
+    L.gate = L.up = nullptr;
+  } else {
+    L.klist = L.kcnt = nullptr;
+    L.rowmask = nullptr;
+    L.gate = cv.take<float>((size_t)T * c.d_ffn);
+    L.up = cv.take<float>((size_t)T * c.d_ffn);
+  }
+  L.bytes = cv.off;
+  return L;
+}
+
+int check_cfg(const sx_model_cfg& c, int P, int T) {
+  if (c.dtype != SX_F32 && c.dtype != SX_BF16) return SX_ERR_DTYPE;
+  if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.head_dim < 2 || c.d_ffn < 1 ||
+      c.vocab < 1 || T < 1 || T > 16384 || P < 0)
+    return SX_ERR_SHAPE;
+  if (c.n_q_heads % c.n_kv_heads != 0 || c.head_dim % 2 != 0) return SX_ERR_SHAPE;
+  if (c.dtype == SX_BF16) {
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (c.head_dim != 128 || !(G == 1 || G == 2 || G == 4 || G == 8)) return SX_ERR_SHAPE;
+    if (c.d_model % 64 != 0 || (c.n_q_heads * c.head_dim) % 64 != 0 || c.d_ffn % 64 != 0) return SX_ERR_SHAPE;
+  } else {
+    if (c.head_dim > 256 || (size_t)P + 2 * (size_t)T > 15360) return SX_ERR_SHAPE;
+  }
+  return SX_OK;
+}
+
+#define SX_TRY(expr)          \
+  do {                        \
+    const int rc_ = (expr);   \
+    if (rc_ != SX_OK) return rc_; \
+  } while (0)
+
+}  // namespace
+
+extern "C" size_t sx_verify_tree_workspace(const sx_model_cfg* cfg, int32_t P, int32_t T) {
+  if (!cfg || check_cfg(*cfg, P, T) != SX_OK) return 0;
+  return carve(*cfg, P, T, nullptr).bytes;
+}
+
+extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t P,
+                              const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T, float* logits_out,
+                              void* tree_k_out, void* tree_v_out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!w || !tree_tokens || !parent_idx || !logits_out || !w->embed || !w->layers || !w->final_norm || !w->lm_head)
+    return SX_ERR_NULL;
+  const sx_model_cfg& c = w->cfg;
+  SX_TRY(check_cfg(c, P, T));
+  if (P > 0 && (!prefix_k || !prefix_v)) return SX_ERR_NULL;
+  if ((tree_k_out == nullptr) != (tree_v_out == nullptr)) return SX_ERR_NULL;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const sx_layer_weights& lw = w->layers[l];
+    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+      return SX_ERR_NULL;
+  }
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
+  const Layout L = carve(c, P, T, workspace);
+  if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  const bool bf = c.dtype == SX_BF16;
+  const size_t es = bf ? 2 : 4;
+  const int d = c.d_model, Hq = c.n_q_heads, Hkv = c.n_kv_heads, Dh = c.head_dim, F = c.d_ffn, V = c.vocab;
+  const int Nq = Hq * Dh, Nkv = Hkv * Dh;
+  int32_t* status = static_cast<int32_t*>(workspace);
+
+  SX_TRY(sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth, L.rope_cs,
+                             status, st));
+  if (bf) SX_TRY(sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), L.klist, L.kcnt, L.rowmask, st));
+  SX_TRY(sx_launch_embed(w->embed, c.dtype, L.tok_s, T, d, L.h, st));
+
+  for (int l = 0; l < c.n_layers; ++l) {
+    const sx_layer_weights& lw = w->layers[l];
+    const size_t kv_layer = (size_t)l * T * Nkv * es, pre_layer = (size_t)l * P * Nkv * es;
+    void* tk = tree_k_out ? static_cast<char*>(tree_k_out) + kv_layer : L.tk;
+    void* tv = tree_v_out ? static_cast<char*>(tree_v_out) + kv_layer : L.tv;
+    const void* pk = P > 0 ? static_cast<const char*>(prefix_k) + pre_layer : nullptr;
+    const void* pv = P > 0 ? static_cast<const char*>(prefix_v) + pre_layer : nullptr;
+
+    SX_TRY(sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+    if (bf) {
+      SX_TRY(sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
+    } else {
+      const int ld = Nq + 2 * Nkv;
+      const float* x = static_cast<const float*>(L.x);
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wq, L.qkv, T, Nq, d, ld, false, st));
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wk, L.qkv + Nq, T, Nkv, d, ld, false, st));
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wv, L.qkv + Nq + Nkv, T, Nkv, d, ld, false, st));
+    }
+    SX_TRY(sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
+    if (bf) {
+      SX_TRY(sx_launch_tree_attn_bf16(L.q, tk, tv, pk, pv, L.klist, L.kcnt, L.rowmask, T, P, Hq, Hkv, L.o, st));
+      SX_TRY(sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, T, Nq, SX_GEMM_RESIDUAL, st));
+      SX_TRY(sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+      SX_TRY(sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, T, d, SX_GEMM_SWIGLU, st));
+      SX_TRY(sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, T, F, SX_GEMM_RESIDUAL, st));
+    } else {
+      SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tk, (const float*)tv, (const float*)pk,
+                                     (const float*)pv, L.par_s, L.depth, T, P, Hq, Hkv, Dh, (float*)L.o, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.o, (const float*)lw.wo, L.h, T, d, Nq, d, true, st));
+      SX_TRY(sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_gate, L.gate, T, F, d, F, false, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_up, L.up, T, F, d, F, false, st));
+      SX_TRY(sx_launch_swiglu_f32(L.gate, L.up, (float*)L.act, (size_t)T * F, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.act, (const float*)lw.w_down, L.h, T, d, F, d, true, st));
+    }
+  }
+  SX_TRY(sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+  if (bf)
+    SX_TRY(sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, T, d, SX_GEMM_STORE, st));
+  else
+    SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, T, V, d, V, false, st));
+  return SX_OK;
+}
+
+// Attention alone: lays out only what it needs at the head of the workspace.
+namespace {
+struct AttnLayout {
+  int32_t *tok_s, *par_s, *depth, *klist, *kcnt;
+  float2* cs;
+  unsigned long long* rowmask;
+  size_t bytes;
+};
+AttnLayout carve_attn(int T, int npt, void* ws) {
+  Carver cv(ws);
+  AttnLayout L;
+  const size_t tiles = (T + npt - 1) / npt;
+  L.tok_s = cv.take<int32_t>(T);
+  L.par_s = cv.take<int32_t>(T);
+  L.depth = cv.take<int32_t>(T);
+  L.cs = cv.take<float2>((size_t)T * 64);
+  L.klist = cv.take<int32_t>(tiles * (size_t)T);
+  L.kcnt = cv.take<int32_t>(tiles);
+  L.rowmask = cv.take<unsigned long long>((size_t)T * ((T + 63) / 64));
+  L.bytes = cv.off;
+  return L;
+}
+bool attn_shape_ok(int T, int Hq, int Hkv) {
+  if (T < 1 || T > 16384 || Hkv < 1 || Hq < 1 || Hq % Hkv != 0) return false;
+  const int G = Hq / Hkv;
+  return G == 1 || G == 2 || G == 4 || G == 8;
+}
+}  // namespace
+
+extern "C" size_t sx_tree_attention_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads) {
+  if (!attn_shape_ok(T, n_q_heads, n_kv_heads)) return 0;
+  return carve_attn(T, sx_attn_nodes_per_tile(n_q_heads, n_kv_heads), nullptr).bytes;
+}
+
+extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
+                                      const void* v_prefix, const int32_t* parent_idx, int32_t T, int32_t P,
+                                      int32_t n_q_heads, int32_t n_kv_heads, void* out, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  if (!q || !k_tree || !v_tree || !parent_idx || !out) return SX_ERR_NULL;
+  if (P > 0 && (!k_prefix || !v_prefix)) return SX_ERR_NULL;
+  if (P < 0 || !attn_shape_ok(T, n_q_heads, n_kv_heads)) return SX_ERR_SHAPE;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
+  const int npt = sx_attn_nodes_per_tile(n_q_heads, n_kv_heads);
+  const AttnLayout L = carve_attn(T, npt, workspace);
+  if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  SX_TRY(sx_launch_tree_prep(nullptr, parent_idx, T, 1, P, 128, 10000.f, L.tok_s, L.par_s, L.depth, L.cs,
+                             static_cast<int32_t*>(workspace), st));
+  SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, L.klist, L.kcnt, L.rowmask, st));
+  return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, P, n_q_heads,
+                                  n_kv_heads, out, st);
+}
+
+extern "C" int sx_check_status(const void* workspace, void* stream) {
+  if (!workspace) return SX_ERR_NULL;
+  int32_t v = 0;
+  hipStream_t st = (hipStream_t)stream;
+  SX_HIP_TRY(hipMemcpyAsync(&v, workspace, sizeof(v), hipMemcpyDeviceToHost, st));
+  SX_HIP_TRY(hipStreamSynchronize(st));
+  return v == SX_OK ? SX_OK : (v == SX_ERR_TREE ? SX_ERR_TREE : SX_ERR_HIP);
+}
+
+extern "C" const char* sx_status_string(int s) {
+  switch (s) {
+    case SX_OK: return "ok";
+    case SX_ERR_NULL: return "a required pointer is NULL";
+    case SX_ERR_SHAPE: return "a size is outside the supported range";
+    case SX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SX_ERR_DTYPE: return "unsupported dtype";
+    case SX_ERR_HIP: return "a HIP call or kernel launch failed";
+    case SX_ERR_TREE: return "tree data invalid: parent index out of order or token outside the vocabulary";
+  }
+  return "unknown status";
+}
+
+extern "C" int sx_version(void) { return 1; }

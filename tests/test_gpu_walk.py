@@ -1,0 +1,114 @@
+"""GPU parity: sx_accept_walk against the oracle's walk (Alg. 1, main loop) -- paths and sampled
+tokens bit-exact on fixtures whose decision margins are safe for fp32."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from helpers import dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-4   # decisions closer than this (in probability mass) may legitimately flip in fp32
+
+
+@pytest.fixture(scope="module")
+def sx():
+    import paper_2406_02532_amd as m
+    return m
+
+
+def _walk(sx, logits_d, tok_d, par_d, t, top_p, seed, pos0):
+    path, toks, n, ws = sx.accept_walk(logits_d, tok_d, par_d, t, top_p, seed, pos0)
+    torch.cuda.synchronize()
+    n = int(n.item())
+    return path[:n].cpu().tolist(), toks[:n].cpu().tolist(), ws
+
+
+def _safe(ref):
+    return all(min(m["m_p"], m["m_u"], m["m_top"]) > MARGIN for m in ref["margins"])
+
+
+@pytest.mark.parametrize("V,T", [(1024, 64), (1000, 40), (8000, 64), (32000, 256), (32768, 32), (50000, 32), (131072, 16)])
+@pytest.mark.parametrize("t,top_p", [(0.6, 0.9), (0.0, 1.0), (1.0, 1.0), (0.3, 0.5)])
+def test_walk_matches_oracle(sx, V, T, t, top_p):
+    tok, par, _ = wl.gen_best_first_tree(T, 4, V, seed=V + T, max_depth=12)
+    logits = wl.gen_crafted_logits(tok, par, V, seed=V + 1, boost=9.0)
+    ld, td, pd = to_dev(logits), to_dev(tok), to_dev(par)
+    checked, longest = 0, 0
+    for seed in range(12):
+        ref = oracle.accept_walk(logits, tok, par, t, top_p, seed=seed, pos0=17)
+        if not _safe(ref):
+            continue
+        path, toks, _ = _walk(sx, ld, td, pd, t, top_p, seed, 17)
+        assert path == ref["path"], (seed, path, ref["path"])
+        assert toks == ref["tokens"]
+        checked += 1
+        longest = max(longest, len(path))
+    assert checked >= 6
+    if t <= 0.6:
+        assert longest >= 3          # sharp distributions: the walk does go down the tree
+
+
+def test_nucleus_with_tied_probabilities(sx):
+    """Equal logits at the nucleus boundary: ties enter in id order (hand-checkable case)."""
+    V = 1024
+    logits = np.full((1, V), -30.0, dtype=np.float32)
+    logits[0, [5, 100, 200, 900]] = [np.log(0.5), np.log(0.2), np.log(0.2), np.log(0.1)]
+    tok, par = np.array([3], np.int32), np.array([-1], np.int32)
+    ld, td, pd = to_dev(logits), to_dev(tok), to_dev(par)
+    for seed in range(40):
+        ref = oracle.accept_walk(logits, tok, par, 1.0, 0.6, seed=seed, pos0=0)
+        if ref["margins"][0]["m_u"] < MARGIN:
+            continue
+        path, toks, _ = _walk(sx, ld, td, pd, 1.0, 0.6, seed, 0)
+        assert toks == ref["tokens"] and toks[0] in (5, 100)      # token 200 ties with 100 but has the higher id
+
+
+def test_duplicate_siblings_and_single_node(sx):
+    tok = np.array([5, 3, 3, 9], np.int32)
+    par = np.array([-1, 0, 0, 1], np.int32)
+    logits = np.full((4, 16), -20.0, dtype=np.float32)
+    logits[0, 3] = logits[1, 9] = logits[2, 1] = logits[3, 2] = 0.0
+    path, toks, _ = _walk(sx, to_dev(logits), to_dev(tok), to_dev(par), 0.0, 1.0, 1, 0)
+    assert path == [0, 1, 3] and toks == [3, 9, 2]
+    path, toks, _ = _walk(sx, to_dev(logits[:1]), to_dev(tok[:1]), to_dev(par[:1]), 0.6, 0.9, 1, 0)
+    assert path == [0] and toks == [3]
+
+
+def test_chain_is_walked_to_its_end(sx):
+    """A chain whose every row points at the next node: the walk visits all T nodes (its maximum)."""
+    T, V = 50, 300
+    tok, par = wl.gen_chain_tree(T, V, seed=4)
+    logits = np.full((T, V), -25.0, dtype=np.float32)
+    for i in range(T - 1):
+        logits[i, tok[i + 1]] = 0.0
+    logits[T - 1, 7] = 0.0
+    path, toks, _ = _walk(sx, to_dev(logits), to_dev(tok), to_dev(par), 0.6, 0.9, 3, 100)
+    assert path == list(range(T)) and toks == tok[1:].tolist() + [7]
+
+
+def test_root_must_be_node_zero(sx):
+    tok = np.array([1, 2], np.int32)
+    par = np.array([0, -1], np.int32)        # node 0 is not a root
+    logits = np.zeros((2, 8), np.float32)
+    _, _, ws = _walk(sx, to_dev(logits), to_dev(tok), to_dev(par), 0.0, 1.0, 0, 0)
+    assert sx.check_status(ws) == -6
+    par = np.array([-1, 0], np.int32)
+    _, _, ws = _walk(sx, to_dev(logits), to_dev(tok), to_dev(par), 0.0, 1.0, 0, 0)
+    assert sx.check_status(ws) == 0
+
+
+def test_plain_categorical_frequencies(sx):
+    """t=1, top_p=1 on a 6-token row over many seeds: chi-square against the exact probabilities."""
+    p = np.array([0.02, 0.4, 0.08, 0.25, 0.05, 0.2])
+    logits = np.log(p).astype(np.float32)[None, :]
+    tok, par = np.array([0], np.int32), np.array([-1], np.int32)
+    ld, td, pd = to_dev(logits), to_dev(tok), to_dev(par)
+    n = 4000
+    outs = [sx.accept_walk(ld, td, pd, 1.0, 1.0, seed, 5)[1] for seed in range(n)]
+    torch.cuda.synchronize()
+    cnt = np.bincount(torch.stack([o[0] for o in outs]).cpu().numpy(), minlength=6)
+    chi2 = ((cnt - n * p) ** 2 / (n * p)).sum()
+    assert chi2 < 25.7
