@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecExec verification hot path on one MI355X.
+
+One step = one pass of the whole path over resident synthetic inputs:
+  sx_verify_tree (80-layer Llama-2-70B-shaped bf16 target, 2048 prefix tokens, a seeded best-first
+  tree of 2048 tokens) -> sx_accept_walk (t=0.6, top-p 0.9) on the logits it produced ->
+  sx_expand_topk (2048 x 32000 draft logits, k=32, best 2048 of 65536).
+Prints one JSON line: verified tree tokens/s, the roofline of the dominant kernel (measured with
+HIP events inside the timed steps) and the CPU oracle timed on a bounded sample of the same work.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C5"])
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (development only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2406_02532_amd as sx
+    import workloads as wl
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    c = wl.CONFIGS[args.workload]
+    cfg = c["cfg"] if not args.layers else c["cfg"].with_layers(args.layers)
+    P, T, k_tree = c["P"], c["T"], c["k"]
+    c4 = wl.CONFIGS["C4"]
+    temperature, top_p = c.get("temperature", 0.6), c.get("top_p", 0.9)
+
+    # ---------------- resident inputs -------------------------------------------------------------
+    t0 = time.time()
+    w = wl.gen_weights(cfg, seed=1, device=dev, progress=lambda l: (l % 10 == 9) and log(f"  weights: layer {l + 1}/{cfg.n_layers}"))
+    torch.cuda.synchronize()
+    nparam = sum(v.numel() for lw in w["layers"] for v in lw.values()) + w["embed"].numel() + w["lm_head"].numel()
+    log(f"weights: {nparam / 1e9:.2f} G parameters ({nparam * 2 / 1e9:.1f} GB) generated on device in {time.time() - t0:.1f}s")
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=2, device=dev)
+    tok, par, _ = wl.gen_best_first_tree(T, k_tree, cfg.vocab, seed=3)
+    stats = wl.tree_stats(par)
+    tok_d, par_d = torch.from_numpy(tok).to(dev), torch.from_numpy(par).to(dev)
+    dl, dc = wl.gen_expand_inputs(c4["N"], c4["V"], seed=4, std=c4["std"], max_depth=c4["max_depth"])
+    dl_d, dc_d = torch.from_numpy(dl).to(dev), torch.from_numpy(dc).to(dev)
+    mw = sx.ModelWeights(cfg, w)
+
+    logits = torch.empty((T, cfg.vocab), dtype=torch.float32, device=dev)
+    ws_v = torch.empty(sx.verify_tree_workspace(cfg, P, T), dtype=torch.uint8, device=dev)
+    ws_w = torch.empty(sx.lib.sx_accept_walk_workspace(T, cfg.vocab), dtype=torch.uint8, device=dev)
+    ws_e = torch.empty(sx.lib.sx_expand_topk_workspace(c4["N"], c4["V"], c4["k"], c4["B"]), dtype=torch.uint8, device=dev)
+    path_o = torch.empty(T, dtype=torch.int32, device=dev)
+    toks_o = torch.empty(T, dtype=torch.int32, device=dev)
+    n_o = torch.empty(1, dtype=torch.int32, device=dev)
+    e_row = torch.empty(c4["B"], dtype=torch.int32, device=dev)
+    e_tok = torch.empty(c4["B"], dtype=torch.int32, device=dev)
+    e_sc = torch.empty(c4["B"], dtype=torch.float32, device=dev)
+    e_n = torch.empty(1, dtype=torch.int32, device=dev)
+
+    def step(seed):
+        sx.verify_tree(mw, pk, pv, tok_d, par_d, logits_out=logits, workspace=ws_v)
+        sx.accept_walk(logits, tok_d, par_d, temperature, top_p, seed, P, path_out=path_o, tokens_out=toks_o,
+                       n_out=n_o, workspace=ws_w)
+        sx.expand_topk(dl_d, dc_d, c4["k"], c4["B"], out_row=e_row, out_token=e_tok, out_cum_logp=e_sc, n_out=e_n,
+                       workspace=ws_e)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert sx.check_status(ws_v) == 0
+
+    launches_per_step = 12 * cfg.n_layers + 16
+    sx.profile_enable(launches_per_step * args.steps + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(100 + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    sx.profile_disable()
+    records = sx.profile_read(launches_per_step * args.steps + 64)
+    ms_per_step = elapsed / args.steps * 1e3
+    value = T / (elapsed / args.steps)
+
+    # ---------------- per-kernel figures -----------------------------------------------------------
+    d, F, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+    Nq, Nkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    depth = np.zeros(T, dtype=np.int64)
+    for i in range(T):
+        depth[i] = 0 if par[i] < 0 else depth[par[i]] + 1
+    flops = {  # algorithmic FLOP per launch
+        "gemm_qkv": 2.0 * T * d * (Nq + 2 * Nkv), "gemm_o": 2.0 * T * Nq * d, "gemm_gateup_swiglu": 4.0 * T * d * F,
+        "gemm_down": 2.0 * T * F * d, "gemm_lmhead": 2.0 * T * d * V,
+        "tree_attn": 4.0 * cfg.n_q_heads * cfg.head_dim * float((P + depth + 1).sum()),
+    }
+    nbytes = {"row_topk": 4.0 * c4["N"] * c4["V"]}   # algorithmic HBM bytes per launch
+    agg = {}
+    for name, ms in records:
+        a = agg.setdefault(name, [0, 0.0])
+        a[0] += 1
+        a[1] += ms
+    kernels = {}
+    for name, (n, tot) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+        e = dict(launches_per_step=n / args.steps, ms_avg=tot / n, ms_per_step=tot / args.steps)
+        if name in flops:
+            e["tflops"] = flops[name] / (tot / n * 1e-3) / 1e12
+            e["frac_mfma_peak"] = e["tflops"] / PEAK_BF16_TFLOPS
+        if name in nbytes:
+            e["gbps"] = nbytes[name] / (tot / n * 1e-3) / 1e9
+            e["frac_hbm_peak"] = e["gbps"] / PEAK_HBM_GBPS
+        kernels[name] = {k: round(v, 6) for k, v in e.items()}
+    total_flop = cfg.n_layers * (flops["gemm_qkv"] + flops["gemm_o"] + flops["gemm_gateup_swiglu"] + flops["gemm_down"]
+                                 + flops["tree_attn"]) + flops["gemm_lmhead"]
+    dom = "gemm_gateup_swiglu"
+    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<2> (gate|up GEMM + SwiGLU, M=%d N=%d K=%d)" % (T, 2 * F, d),
+                    achieved=round(kernels[dom]["tflops"], 3), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 5), traffic=None,
+                    flop_per_launch=flops[dom], ms_avg=kernels[dom]["ms_avg"])
+
+    out = dict(metric="verified tree tokens/s per target forward (T=%d)" % T, value=round(value, 2), unit="tokens/s",
+               n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload="%s: %d-layer Llama-2-70B-shaped target (d=%d, %d/%d heads x %d, FFN %d, vocab %d), "
+                           "prefix %d, seeded best-first tree of %d tokens (k=%d), then accept_walk t=%.1f top-p %.1f and "
+                           "expand_topk %dx%d k=%d B=%d" % (args.workload, cfg.n_layers, d, cfg.n_q_heads, cfg.n_kv_heads,
+                                                              cfg.head_dim, F, V, P, T, k_tree, temperature, top_p,
+                                                              c4["N"], c4["V"], c4["k"], c4["B"]),
+                           tree=dict(max_depth=stats["max_depth"], mean_ancestors=round(stats["mean_ancestors"], 2)),
+                           parameters_GB=round(nparam * 2 / 1e9, 1)),
+               tflops=round(total_flop / (elapsed / args.steps) / 1e12, 2),
+               frac_mfma_peak=round(total_flop / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 5),
+               topk_hbm_gbps=kernels.get("row_topk", {}).get("gbps"),
+               accepted_tokens_last_step=int(n_o.item()),
+               roofline=roofline, kernels=kernels)
+
+    # ---------------- CPU oracle on a bounded sample ---------------------------------------------------
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample: the first 64 tree
+    nodes (an ancestor-closed sub-tree) through 1 and through 2 layers (+ lm_head) to separate
+    per-layer from per-call cost, 128 rows of the draft expansion, one acceptance walk; scaled to
+    the full step and expressed in the metric's unit."""
+    import numpy as np
+    import torch
+
+    import oracle
+    Ts, Ns = min(64, T), min(128, c4["N"])
+    cpu = lambda t: t.detach().to("cpu")
+    log("cpu_baseline: copying 2 layers to the host ...")
+    L2 = min(2, cfg.n_layers)
+    wc = dict(embed=cpu(w["embed"]), final_norm=cpu(w["final_norm"]), lm_head=cpu(w["lm_head"]),
+              layers=[{k: cpu(v) for k, v in w["layers"][l].items()} for l in range(L2)])
+    pkc, pvc = cpu(pk[:L2]), cpu(pv[:L2])
+    times = []
+    for L in range(1, L2 + 1):
+        t0 = time.perf_counter()
+        oracle.verify_tree(cfg.with_layers(L), dict(wc, layers=wc["layers"][:L]), pkc[:L], pvc[:L], tok[:Ts], par[:Ts],
+                           act_round="bf16")
+        times.append(time.perf_counter() - t0)
+        log(f"cpu_baseline: oracle verify_tree, {L} layer(s), {Ts} nodes: {times[-1]:.2f}s")
+    t_layer = times[1] - times[0] if L2 == 2 else times[0]
+    t_rest = max(times[0] - t_layer, 0.0)
+    t0 = time.perf_counter()
+    oracle.expand_topk(dl[:Ns], dc[:Ns], c4["k"], c4["B"])
+    t_exp = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.accept_walk(dl[:T], tok, par, temperature, top_p, seed=1, pos0=P)   # draft logits stand in as rows to sample from
+    t_walk = time.perf_counter() - t0
+    step_s = (cfg.n_layers * t_layer + t_rest) * (T / Ts) + t_exp * (c4["N"] / Ns) + t_walk
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads()])
+    except Exception:
+        cores = torch.get_num_threads()
+    return dict(value=round(T / step_s, 4), unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"first {Ts} of {T} tree nodes through 1 and 2 of {cfg.n_layers} layers + lm_head "
+                       f"({times[0]:.1f}s, {times[-1]:.1f}s), {Ns} of {c4['N']} expansion rows ({t_exp:.1f}s), one walk "
+                       f"({t_walk:.2f}s); scaled linearly to the full step = {step_s:.0f}s",
+                seconds_measured=round(sum(times) + t_exp + t_walk, 2))
+
+
+if __name__ == "__main__":
+    main()

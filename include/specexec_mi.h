@@ -189,6 +189,23 @@ int sx_tree_attention_bf16(const void *q, const void *k_tree, const void *v_tree
                            int32_t T, int32_t P, int32_t n_q_heads, int32_t n_kv_heads, void *out,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Optional kernel timing for callers that measure (not part of the method).  Between
+ * sx_profile_enable and sx_profile_disable the three calls above record a pair of HIP events
+ * on the caller's stream around each kernel launch, up to max_records pairs (events are
+ * created here, once).  sx_profile_read waits for the recorded events, returns for each pair
+ * its kernel class (sx_kernel_class) and elapsed milliseconds, and clears the log.
+ * One process-wide log; not thread-safe.
+ * ---------------------------------------------------------------------------------------- */
+typedef enum sx_kernel_class {
+  SX_KC_PREP = 1, SX_KC_EMBED, SX_KC_NORM, SX_KC_GEMM_QKV, SX_KC_ROPE, SX_KC_ATTN, SX_KC_GEMM_O,
+  SX_KC_GEMM_GATEUP, SX_KC_GEMM_DOWN, SX_KC_GEMM_LMHEAD, SX_KC_ROW_TOPK, SX_KC_SELECT, SX_KC_WALK,
+  SX_KC_F32_PATH
+} sx_kernel_class;
+int sx_profile_enable(int32_t max_records);
+int sx_profile_disable(void);
+int sx_profile_read(int32_t *classes, float *milliseconds, int32_t capacity, int32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -122,14 +122,18 @@ def tree_attention(q, k_tree, v_tree, k_prefix, v_prefix, parent):
     return out
 
 
-def verify_tree(cfg, w, prefix_k, prefix_v, tokens, parent, act_round=None):
+def verify_tree(cfg, w, prefix_k, prefix_v, tokens, parent, act_round=None, perturb=0.0):
     """FORWARD(tau, theta_target) of Alg. 1: logits [T, vocab], row i = distribution of the
     token that follows node i.  Also returns the tree's own K/V per layer.
 
     cfg: object with n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab,
     rope_base, rms_eps.  w: dict(embed, layers[list of dict], final_norm, lm_head), linear
     weights row-major [out, in] (y = x W^T), no biases.  prefix_k/v: [L, P, Hkv, Dh], K
-    already rotated at positions 0..P-1.  Node i sits at position P + depth(i)."""
+    already rotated at positions 0..P-1.  Node i sits at position P + depth(i).
+
+    ``perturb`` (default 0) multiplies the embedded inputs by 1 + perturb * N(0,1): a knob for
+    measuring how far two equally valid bf16 evaluations of the same model drift apart when
+    their arithmetic differs in the last bits (the rounding-flip noise floor)."""
     R = _rounder(act_round)
     tokens = np.asarray(tokens)
     parent = np.asarray(parent)
@@ -139,6 +143,8 @@ def verify_tree(cfg, w, prefix_k, prefix_v, tokens, parent, act_round=None):
     P = prefix_k.shape[1]
     pos = P + tree_depths(parent)
     h = _f64(w["embed"])[tokens]                                      # [T, d]
+    if perturb:
+        h = h * (1.0 + perturb * np.random.default_rng(0).standard_normal(h.shape))
     tk, tv = [], []
     for l in range(cfg.n_layers):
         lw = w["layers"][l]

@@ -10,7 +10,8 @@ import torch
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
 EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
-           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16"]
+           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
+           "sx_profile_enable", "sx_profile_disable", "sx_profile_read"]
 
 SX_F32, SX_BF16 = 0, 1
 
@@ -69,10 +70,19 @@ def _load():
     L.sx_tree_attention_workspace.argtypes = [i32, i32, i32]
     L.sx_tree_attention_bf16.restype = C.c_int
     L.sx_tree_attention_bf16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.sx_profile_enable.restype = C.c_int
+    L.sx_profile_enable.argtypes = [i32]
+    L.sx_profile_disable.restype = C.c_int
+    L.sx_profile_read.restype = C.c_int
+    L.sx_profile_read.argtypes = [vp, vp, i32, vp]
     return L
 
 
 lib = _load()
+
+KERNEL_CLASSES = {1: "prep", 2: "embed", 3: "rmsnorm", 4: "gemm_qkv", 5: "rope", 6: "tree_attn", 7: "gemm_o",
+                  8: "gemm_gateup_swiglu", 9: "gemm_down", 10: "gemm_lmhead", 11: "row_topk", 12: "global_select",
+                  13: "accept_walk", 14: "f32_path"}
 
 
 def status_string(code: int) -> str:
@@ -223,3 +233,20 @@ def tree_attention_bf16(q, k_tree, v_tree, k_prefix, v_prefix, parent_idx, out=N
 
 def check_status(workspace, stream=None) -> int:
     return lib.sx_check_status(_ptr(workspace), _stream(stream))
+
+
+def profile_enable(max_records: int):
+    _check(lib.sx_profile_enable(max_records), "sx_profile_enable")
+
+
+def profile_disable():
+    lib.sx_profile_disable()
+
+
+def profile_read(capacity: int = 1 << 16):
+    """Returns a list of (kernel class name, milliseconds) and clears the log."""
+    tags = (C.c_int32 * capacity)()
+    ms = (C.c_float * capacity)()
+    n = C.c_int32(0)
+    _check(lib.sx_profile_read(tags, ms, capacity, C.byref(n)), "sx_profile_read")
+    return [(KERNEL_CLASSES.get(tags[i], str(tags[i])), ms[i]) for i in range(n.value)]

@@ -7,7 +7,7 @@
 // whose probes are block reductions in a fixed order, so a given input always gives the same path:
 //   * nucleus threshold: the largest float bit pattern K with  sum{e >= K} >= top_p * Z;
 //   * draw: the largest id Y with  sum{nucleus, id < Y} <= u * mass  (inverse CDF in id order).
-#include "common.h"
+#include "kernels.h"
 
 namespace {
 
@@ -209,11 +209,13 @@ extern "C" int sx_accept_walk(const float* logits, const float* draft_probs, con
 #define SX_WALK(NT, ITEMS)                                                                                     \
   accept_walk_kernel<NT, ITEMS><<<1, NT, 0, st>>>(logits, tree_tokens, parent_idx, T, V, temperature, top_p, \
                                                   (unsigned long long)seed, pos0, path_out, tokens_out, n_out, ebuf, status)
+  sx_prof_begin(SX_K_WALK, st);
   if (V <= 1024) SX_WALK(512, 2);
   else if (V <= 8192) SX_WALK(512, 16);
   else if (V <= 32768) SX_WALK(512, 64);
   else SX_WALK(1024, 0);
 #undef SX_WALK
+  sx_prof_end(st);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

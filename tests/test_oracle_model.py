@@ -368,3 +368,22 @@ def test_round_bf16_matches_torch():
     x = np.concatenate([x, [1.00390625, 1.01171875, 0.0, -0.0]])   # exact ties: round to even
     ref = torch.from_numpy(x).float().to(torch.bfloat16).double().numpy()
     assert np.array_equal(oracle.round_bf16(x), ref)
+
+
+def test_bf16_rounding_flip_noise_floor():
+    """Why bf16 parity cannot be much tighter than ~1e-2 of the logit scale: the oracle evaluated
+    twice with bf16 activations, the second time with inputs nudged by 3e-6 (fp32-level noise),
+    disagrees with itself far more than the nudge -- flipped roundings cascade from stage to stage.
+    With exact (fp64) activations the same nudge stays a nudge."""
+    cfg = ModelCfg(1, 512, 4, 4, 128, 1376, 2000, dtype="bf16")
+    w = gen_weights(cfg, seed=41)
+    r = np.random.default_rng(42)
+    pk = r.standard_normal((1, 64, 4, 128))
+    pv = r.standard_normal((1, 64, 4, 128))
+    tok, par = gen_uniform_tree(48, cfg.vocab, seed=43)
+    a = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16")["logits"]
+    b = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16", perturb=3e-6)["logits"]
+    c = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
+    d = oracle.verify_tree(cfg, w, pk, pv, tok, par, perturb=3e-6)["logits"]
+    assert np.abs(c - d).max() < 1e-4 * a.std()
+    assert np.abs(a - b).max() > 5e-3 * a.std()

@@ -291,13 +291,23 @@ def gen_expand_inputs(N: int, V: int, seed: int, std: float = 3.0, max_depth: in
 
 
 def gen_crafted_logits(tokens: np.ndarray, parent: np.ndarray, V: int, seed: int,
-                       boost: float = 8.0) -> np.ndarray:
+                       boost: float = 8.0, sharp: bool = False) -> np.ndarray:
     """Target-logit stand-in that makes the acceptance walk traverse several tree levels on a
     random-init model: row i is N(0,1) noise plus ``boost`` on the token of one randomly
-    chosen child of node i (leaves get pure noise)."""
+    chosen child of node i (leaves get pure noise).
+
+    ``sharp`` mimics the peaked next-token distributions of trained LLMs (Fig. 2: the top 1-4
+    tokens hold 90-98 % of the mass): the noise floor is pushed 12 units down and every row
+    gets four more random tokens with logits uniform in [0, boost), so the nucleus holds a
+    handful of well-separated tokens at every node, leaves included."""
     T = len(tokens)
     r = _rng(seed, 6)
     logits = r.standard_normal((T, V), dtype=np.float32)
+    if sharp:
+        logits -= np.float32(12.0)
+        for i in range(T):
+            alt = r.choice(V, size=min(4, V), replace=False)
+            logits[i, alt] = r.uniform(0.0, boost, size=len(alt)).astype(np.float32)
     kids = [[] for _ in range(T)]
     for i in range(T):
         if parent[i] >= 0:
@@ -305,5 +315,5 @@ def gen_crafted_logits(tokens: np.ndarray, parent: np.ndarray, V: int, seed: int
     for i in range(T):
         if kids[i]:
             c = kids[i][int(r.integers(0, len(kids[i])))]
-            logits[i, tokens[c]] += np.float32(boost)
+            logits[i, tokens[c]] = np.float32(boost) + (np.float32(0.0) if sharp else logits[i, tokens[c]])
     return logits
