@@ -4,11 +4,13 @@
 // Tiling.  A workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile; each wave a 128 x 128
 // quadrant = 4 x 4 MFMA blocks, 256 fp32 accumulators per lane.  K is walked in slabs of 64:
 // the 256x64 X slab and the 256x64 W slab (32 KB each) are double-buffered in LDS (128 KB of the
-// 160 KB), fetched global -> registers one slab ahead and written to LDS after the current slab's
-// MFMAs.  Both operands are K-contiguous in memory, which is exactly the per-lane layout the MFMA
+// 160 KB), fetched global -> registers two slabs ahead (two register sets) and written to LDS after
+// the current slab's MFMAs.  Both operands are K-contiguous in memory, which is exactly the per-lane layout the MFMA
 // wants (8 consecutive k per lane), so LDS rows are plain 128-byte row segments; the 16-byte
-// chunk index is XOR-swizzled with (row & 7) so that the 8 lanes served per LDS cycle hit 8
-// different bank groups on both the write and the read side.
+// chunk index is XOR-swizzled with (row >> 1) & 7: the LDS serves 16 lanes x 16 bytes per cycle
+// (64 banks), and with this swizzle 16 consecutive rows reading the same k chunk -- and 16
+// consecutive lanes writing two rows -- touch 16 different bank groups (measured: ~220 B/clk per
+// CU against ~140 B/clk for a swizzle by row & 7).
 //
 // XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
 // Tile index = xcd * chunk + id / 8 with tiles ordered M-fastest, so the workgroups resident on
@@ -38,7 +40,7 @@ struct GemmArgs {
   int tilesM, tilesN, chunk;
 };
 
-__device__ __forceinline__ int lds_off(int row, int kchunk) { return row * (BK * 2) + ((kchunk ^ (row & 7)) << 4); }
+__device__ __forceinline__ int lds_off(int row, int kchunk) { return row * (BK * 2) + ((kchunk ^ ((row >> 1) & 7)) << 4); }
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
@@ -55,30 +57,41 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   const int tile_m = lin % a.tilesM, tile_n = lin / a.tilesM;
 
   // ---- global source rows of this lane: 8 rows of X and 8 rows of W, one 16-byte chunk each -------
+  // Row r0 + 32 i of the slab.  All lanes of the block share the 32-row group i, and a group never
+  // straddles two weight matrices (segment sizes are multiples of 32), so the matrix base pointer is
+  // uniform per i (scalar registers) and only a 32-bit byte offset is kept per lane.
   const int kc = tid & 7;         // chunk within the 64-wide slab
   const int r0 = tid >> 3;        // rows r0 + 32*i
-  const unsigned short* xrow[8];
-  const unsigned short* wrow[8];
+  const char* xbase = reinterpret_cast<const char*>(a.X);
+  const char* wbase[8];
+  unsigned xoff[8], woff[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int r = r0 + 32 * i;
     int m = tile_m * BM + r;
     m = m < a.M ? m : a.M - 1;
-    xrow[i] = a.X + (size_t)m * a.K + kc * 8;
-    const unsigned short* w;
+    xoff[i] = ((unsigned)m * (unsigned)a.K + kc * 8) * 2u;
     if (MODE == SX_GEMM_SWIGLU) {
-      const int g = r >> 5;                                  // 32-row group: even = gate, odd = up
-      int f = tile_n * (BN / 2) + (g >> 1) * 32 + (r & 31);
+      int f = tile_n * (BN / 2) + (i >> 1) * 32 + (r & 31);  // group i: even = gate, odd = up
       f = f < a.N ? f : a.N - 1;
-      w = ((g & 1) ? a.W1 : a.W0) + (size_t)f * a.K;
+      wbase[i] = reinterpret_cast<const char*>((i & 1) ? a.W1 : a.W0);
+      woff[i] = ((unsigned)f * (unsigned)a.K + kc * 8) * 2u;
     } else {
+      const int g0 = min(tile_n * BN + 32 * i, a.N - 1);     // first row of the group decides the matrix
       int n = tile_n * BN + r;
       n = n < a.N ? n : a.N - 1;
-      if (n < a.n0) w = a.W0 + (size_t)n * a.K;
-      else if (n < a.n0 + a.n1) w = a.W1 + (size_t)(n - a.n0) * a.K;
-      else w = a.W2 + (size_t)(n - a.n0 - a.n1) * a.K;
+      const unsigned short* base = a.W0;
+      int first = 0;
+      if (g0 >= a.n0 + a.n1) {
+        base = a.W2;
+        first = a.n0 + a.n1;
+      } else if (g0 >= a.n0) {
+        base = a.W1;
+        first = a.n0;
+      }
+      wbase[i] = reinterpret_cast<const char*>(base);
+      woff[i] = ((unsigned)(n - first) * (unsigned)a.K + kc * 8) * 2u;
     }
-    wrow[i] = w + kc * 8;
   }
 
   f32x16 acc[4][4];
@@ -89,51 +102,107 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4 rx[8], rw[8];
-  auto fetch = [&](int kt) {
+  // Two register sets stage the global -> LDS traffic two K slabs ahead: the slab fetched during
+  // iteration kt is written to LDS at the end of iteration kt+1 and consumed in iteration kt+2, so
+  // a fetch has two slabs' worth of MFMA time (~1.7 us) to come back from HBM.
+  u32x4 rx0[8], rw0[8], rx1[8], rw1[8];
+  // byte offsets of this lane's fragment rows inside a stage (chunk 0; the chunk index is XORed in).
+  // Every fragment row of a lane has the same (row >> 1) & 7 = (lane >> 1) & 7.
+  int aoff[4], boff[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      rx[i] = *reinterpret_cast<const u32x4*>(xrow[i] + (size_t)kt * BK);
-      rw[i] = *reinterpret_cast<const u32x4*>(wrow[i] + (size_t)kt * BK);
-    }
-  };
-  auto stash = [&](int buf) {
-    char* xs = lds + buf * 2 * kSlabBytes;
-    char* ws = xs + kSlabBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int off = lds_off(r0 + 32 * i, kc);
-      *reinterpret_cast<u32x4*>(xs + off) = rx[i];
-      *reinterpret_cast<u32x4*>(ws + off) = rw[i];
-    }
-  };
+  for (int i = 0; i < 4; ++i) {
+    aoff[i] = (wm * 128 + i * 32 + l32) * (BK * 2);
+    boff[i] = kSlabBytes + (wn * 128 + i * 32 + l32) * (BK * 2);
+  }
+  const int sw = (lane >> 1) & 7;
+  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
 
+#define SX_FETCH(RX, RW, KT_, I0)                                                                  \
+  _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
+    RX[i] = *reinterpret_cast<const u32x4*>(xbase + (size_t)(KT_) * (BK * 2) + xoff[i]);          \
+    RW[i] = *reinterpret_cast<const u32x4*>(wbase[i] + (size_t)(KT_) * (BK * 2) + woff[i]);       \
+  }
+#define SX_STASH(RX, RW, BUF_, I0)                                                                 \
+  _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
+    const int off = lds_off(r0 + 32 * i, kc);                                                     \
+    *reinterpret_cast<u32x4*>(lds + (BUF_) * 2 * kSlabBytes + off) = RX[i];                       \
+    *reinterpret_cast<u32x4*>(lds + (BUF_) * 2 * kSlabBytes + kSlabBytes + off) = RW[i];          \
+  }
+#define SX_READ(STAGE, A, B, ks)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+    const int c = ((2 * (ks) + lh) ^ sw) << 4;                                                    \
+    A[i] = *reinterpret_cast<const bf16x8*>((STAGE) + aoff[i] + c);                               \
+    B[i] = *reinterpret_cast<const bf16x8*>((STAGE) + boff[i] + c);                               \
+  }
+#define SX_MMA(A, B)                                                                               \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)      \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[i], B[j], acc[i][j], 0, 0, 0);
+// One K slab: 4 k-steps of 16 MFMAs.  Fragments of step ks+1 are read while step ks multiplies; the
+// global fetch of the slab two ahead and the LDS write of the slab one ahead are dealt out between
+// the MFMA groups so that their issue slots hide under matrix-core time.
+// Issue order requested from the scheduler for one slab (masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS
+// write, 0x020 global read): both leading fragment sets, then 16 rounds of 4 MFMAs each carrying
+// one LDS write and one global read; rounds 4-11 also carry the two fragment reads that refill the
+// set the preceding k-step has just finished with.
+#define SX_SCHED                                                                                   \
+  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);                                              \
+  _Pragma("unroll") for (int r_ = 0; r_ < 16; ++r_) {                                             \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                             \
+    if (r_ >= 4 && r_ < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                     \
+    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                             \
+    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                             \
+  }
+#define SX_SLAB(STAGE, FRX, FRW, FKT, SRX, SRW, SBUF)                                              \
+  SX_READ(STAGE, fa0, fb0, 0)                                                                      \
+  SX_READ(STAGE, fa1, fb1, 1)                                                                      \
+  SX_FETCH(FRX, FRW, FKT, 0)                                                                       \
+  SX_MMA(fa0, fb0)                                                                                 \
+  SX_READ(STAGE, fa0, fb0, 2)                                                                      \
+  SX_STASH(SRX, SRW, SBUF, 0)                                                                      \
+  SX_MMA(fa1, fb1)                                                                                 \
+  SX_READ(STAGE, fa1, fb1, 3)                                                                      \
+  SX_FETCH(FRX, FRW, FKT, 4)                                                                       \
+  SX_MMA(fa0, fb0)                                                                                 \
+  SX_STASH(SRX, SRW, SBUF, 4)                                                                      \
+  SX_MMA(fa1, fb1)                                                                                 \
+  SX_SCHED
+
+  // The loop body is branch-free: past the end of K it re-fetches the last slab and writes it to a
+  // stage nobody reads again, which costs nothing and keeps each slab one schedulable block.
   const int KT = a.K / BK;
-  fetch(0);
-  stash(0);
+  const int last = KT - 1;
+  SX_FETCH(rx0, rw0, 0, 0)
+  SX_FETCH(rx0, rw0, 0, 4)
+  SX_STASH(rx0, rw0, 0, 0)
+  SX_STASH(rx0, rw0, 0, 4)
+  SX_FETCH(rx1, rw1, min(1, last), 0)
+  SX_FETCH(rx1, rw1, min(1, last), 4)
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    if (kt + 1 < KT) fetch(kt + 1);
-    const char* xs = lds + (kt & 1) * 2 * kSlabBytes;
-    const char* ws = xs + kSlabBytes;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[4], bf[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wm * 128 + i * 32 + l32, 2 * ks + lh));
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        bf[j] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wn * 128 + j * 32 + l32, 2 * ks + lh));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) stash((kt + 1) & 1);
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    // even slab: in LDS stage 0; set 0 is free (fetch slab kt+2 into it), set 1 holds slab kt+1 (-> stage 1)
+    SX_SLAB(lds, rx0, rw0, min(kt + 2, last), rx1, rw1, 1)
+    __syncthreads();
+    // odd slab: in LDS stage 1; set 1 is free (fetch slab kt+3), set 0 holds slab kt+2 (-> stage 0)
+    SX_SLAB(lds + 2 * kSlabBytes, rx1, rw1, min(kt + 3, last), rx0, rw0, 0)
     __syncthreads();
   }
+  if (kt < KT) {  // odd slab count: the last one sits in stage 0
+    SX_READ(lds, fa0, fb0, 0)
+    SX_MMA(fa0, fb0)
+    SX_READ(lds, fa0, fb0, 1)
+    SX_MMA(fa0, fb0)
+    SX_READ(lds, fa0, fb0, 2)
+    SX_MMA(fa0, fb0)
+    SX_READ(lds, fa0, fb0, 3)
+    SX_MMA(fa0, fb0)
+  }
+#undef SX_FETCH
+#undef SX_STASH
+#undef SX_READ
+#undef SX_MMA
+#undef SX_SLAB
+#undef SX_SCHED
 
   // ---- epilogue.  acc[i][j][e]: row = 32i + 8(e/4) + 4*lh + e%4, col = 32j + l32 within the quadrant --
   const int mbase = tile_m * BM + wm * 128;

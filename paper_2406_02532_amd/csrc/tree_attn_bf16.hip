@@ -10,7 +10,7 @@
 // node's own ancestors.  Work on the tree part is therefore proportional to what is attended.
 //
 // Data flow per key tile (flash-style online softmax):
-//   K rows  -> LDS [key][d], 16-byte chunks XOR-swizzled by key;
+//   K rows  -> LDS [key][d], 16-byte chunks XOR-swizzled by key & 15 (16 lanes x 16 B per LDS cycle);
 //   V rows  -> LDS transposed [d][key slot], packed on the fly from 4-byte column pairs;
 //   S^T = K Q^T   (MFMA 32x32x16: A = K from LDS, B = Q held in registers for the whole kernel).
 //         Computing the transpose puts a query row in ONE lane pair (l, l^32): max and sum need a
@@ -41,8 +41,14 @@ struct AttnArgs {
   int T, P, Hq, Hkv, G, npt, W64;
 };
 
-__device__ __forceinline__ int ks_off(int key, int chunk) { return key * (DH * 2) + ((chunk ^ (key & 7)) << 4); }
+__device__ __forceinline__ int ks_off(int key, int chunk) { return key * (DH * 2) + ((chunk ^ (key & 15)) << 4); }
 __device__ __forceinline__ int vt_off(int d, int chunk) { return d * (KTILE * 2) + ((chunk ^ ((d ^ (d >> 3)) & 7)) << 4); }
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_cvt_pk_bf16_f32
+  f32x2 t = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
+}
 
 __global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char Ks[KTILE * DH * 2];
@@ -70,44 +76,65 @@ __global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
   }
   const int cnt = a.kcnt[tile];
   const int nPre = (a.P + KTILE - 1) / KTILE;
-  const int nTiles = nPre + (cnt + KTILE - 1) / KTILE;
+  const int nTree = (cnt + KTILE - 1) / KTILE;
   const int* kl = a.klist + (size_t)tile * a.T;
   const unsigned long long* rm = a.rowmask + (size_t)(row_ok ? node : 0) * a.W64;
+  const unsigned rowB = (unsigned)a.Hkv * DH * 2;  // bytes between consecutive key rows
 
-  // ---- prefetch registers ---------------------------------------------------------------------------
+  // ---- staging registers for the next tile ------------------------------------------------------------
+  // K: lane fetches the 16-byte chunk (tid & 15) of keys (tid >> 4) + 16 i.  V: wave w fetches, for
+  // the 16 key slots it transposes, the 4-byte column pair `lane` of each.  Slots past the end of
+  // the key list re-read the last valid key (finite data); the mask keeps them out of the softmax.
   u32x4 rk[4];
   unsigned rv[2][8];
   unsigned long long rmask = 0ull;
-  auto fetch = [&](int t) {
-    const bool pre = t < nPre;
-    const int base = pre ? t * KTILE : (t - nPre) * KTILE;
-    const int count = pre ? min(KTILE, a.P - base) : min(KTILE, cnt - base);
-    const unsigned short* ksrc = pre ? a.k_prefix : a.k_tree;
-    const unsigned short* vsrc = pre ? a.v_prefix : a.v_tree;
+  const unsigned kcol = (unsigned)kvh * DH * 2 + (tid & 15) * 16;
+  const unsigned vcol = (unsigned)kvh * DH * 2 + lane * 4;
+  auto fetch_prefix = [&](int t) {
+    const int base = t * KTILE;
+    const int last = a.P - 1;
+    const char* kb = reinterpret_cast<const char*>(a.k_prefix);
+    const char* vb = reinterpret_cast<const char*>(a.v_prefix);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int c = (tid >> 4) + 16 * i;
-      u32x4 t4 = {0u, 0u, 0u, 0u};
-      if (c < count) {
-        const int row = pre ? base + c : kl[base + c];
-        t4 = *reinterpret_cast<const u32x4*>(ksrc + ((size_t)row * a.Hkv + kvh) * DH + (tid & 15) * 8);
-      }
-      rk[i] = t4;
+      const int row = min(base + (tid >> 4) + 16 * i, last);
+      rk[i] = *reinterpret_cast<const u32x4*>(kb + (size_t)((unsigned)row * rowB + kcol));
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int c = 16 * wave + (j >> 2) * 8 + 4 * h + (j & 3);
-        unsigned v = 0u;
-        if (c < count) {
-          const int row = pre ? base + c : kl[base + c];
-          v = *reinterpret_cast<const unsigned*>(vsrc + ((size_t)row * a.Hkv + kvh) * DH + lane * 2);
-        }
-        rv[h][j] = v;
+        const int row = min(base + 16 * wave + (j >> 2) * 8 + 4 * h + (j & 3), last);
+        rv[h][j] = *reinterpret_cast<const unsigned*>(vb + (size_t)((unsigned)row * rowB + vcol));
       }
-    if (pre) rmask = count == KTILE ? ~0ull : ((1ull << count) - 1ull);
-    else rmask = row_ok ? rm[t - nPre] : 0ull;
+    const int count = min(KTILE, a.P - base);
+    rmask = count == KTILE ? ~0ull : ((1ull << count) - 1ull);
+  };
+  auto fetch_tree = [&](int t) {
+    const int base = t * KTILE;
+    const int last = cnt - 1;
+    const char* kb = reinterpret_cast<const char*>(a.k_tree);
+    const char* vb = reinterpret_cast<const char*>(a.v_tree);
+    int krow[4], vrow[2][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) krow[i] = kl[min(base + (tid >> 4) + 16 * i, last)];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) vrow[h][j] = kl[min(base + 16 * wave + (j >> 2) * 8 + 4 * h + (j & 3), last)];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      rk[i] = *reinterpret_cast<const u32x4*>(kb + (size_t)((unsigned)krow[i] * rowB + kcol));
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        rv[h][j] = *reinterpret_cast<const unsigned*>(vb + (size_t)((unsigned)vrow[h][j] * rowB + vcol));
+    rmask = row_ok ? rm[t] : 0ull;
+  };
+  auto fetch = [&](int t) {
+    if (t < nPre) fetch_prefix(t);
+    else fetch_tree(t - nPre);
   };
   auto stash = [&]() {
 #pragma unroll
@@ -127,15 +154,21 @@ __global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
   };
 
   // ---- running state of this lane's row ----------------------------------------------------------
+  // m_ref is the reference the exponentials are taken against.  It follows the running maximum
+  // lazily: only when a tile's maximum exceeds it by more than kSlack (in exponent bits) are the
+  // accumulators rescaled, so probabilities stay below 2^kSlack and most tiles skip the rescale.
   const float NEG_INF = -__builtin_huge_valf();
   const float c2 = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
-  float m_run = NEG_INF, l_run = 0.f;
+  constexpr float kSlack = 8.0f;
+  const float slack_raw = kSlack / c2;
+  float m_ref = NEG_INF, l_run = 0.f;
   f32x16 oacc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
 
+  const int nTiles = nPre + nTree;
   if (nTiles > 0) fetch(0);
   for (int t = 0; t < nTiles; ++t) {
     __syncthreads();  // everyone is done reading the previous tile
@@ -158,38 +191,52 @@ __global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
     }
     // ---- online softmax for this row ------------------------------------------------------------
     float mx = NEG_INF;
+    if (mask != (~0ull >> (4 * lh))) {  // some key slots are not this row's: only tail and tree tiles
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int bit = 32 * kb + 8 * (e >> 2) + (e & 3);  // + 4*lh, already shifted out of `mask`
+          st[kb][e] = ((mask >> bit) & 1ull) ? st[kb][e] : NEG_INF;
+        }
+    }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int bit = 32 * kb + 8 * (e >> 2) + (e & 3);  // + 4*lh, already shifted out of `mask`
-        const float s = ((mask >> bit) & 1ull) ? st[kb][e] : NEG_INF;
-        st[kb][e] = s;
-        mx = fmaxf(mx, s);
-      }
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c2);
-    m_run = m_new;
+    float alpha = 1.0f;
+    if (mx > m_ref + slack_raw) {  // also taken on the first tile (m_ref = -inf)
+      alpha = __builtin_amdgcn_exp2f((m_ref - mx) * c2);
+      m_ref = mx;
+    }
+    const float m_use = (m_ref == NEG_INF) ? 0.f : m_ref;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+    }
     float psum = 0.f;
     bf16x8 phi[4], plo[4];
+    const float mc = m_use * c2;
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
+      u32x4 hi4, lo4;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float p = __builtin_amdgcn_exp2f((st[s4 >> 1][8 * (s4 & 1) + j] - m_use) * c2);
-        psum += p;
-        const __bf16 hi = (__bf16)p;
-        phi[s4][j] = hi;
-        plo[s4][j] = (__bf16)(p - (float)hi);
+      for (int jp = 0; jp < 4; ++jp) {
+        const float p0 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp] * c2 - mc);
+        const float p1 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp + 1] * c2 - mc);
+        psum += p0 + p1;
+        const unsigned h2 = cvt_pk_bf16(p0, p1);
+        hi4[jp] = h2;
+        lo4[jp] = cvt_pk_bf16(p0 - __uint_as_float(h2 << 16), p1 - __uint_as_float(h2 & 0xFFFF0000u));
       }
+      phi[s4] = __builtin_bit_cast(bf16x8, hi4);
+      plo[s4] = __builtin_bit_cast(bf16x8, lo4);
     }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
+    l_run += psum;
     // ---- O^T += V^T P^T : oacc[db][e] = out(d = 32db + 8(e/4) + 4lh + e%4, this lane's row) ------------
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4)
@@ -212,8 +259,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
       for (int g = 0; g < 4; ++g) {
         const int d = 32 * db + 8 * g + 4 * lh;
         u32x2 w;
-        w[0] = pack_bf16x2(oacc[db][4 * g + 0] * inv, oacc[db][4 * g + 1] * inv);
-        w[1] = pack_bf16x2(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
+        w[0] = cvt_pk_bf16(oacc[db][4 * g + 0] * inv, oacc[db][4 * g + 1] * inv);
+        w[1] = cvt_pk_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
         *reinterpret_cast<u32x2*>(op + d) = w;
       }
   }
