@@ -166,7 +166,7 @@ def verify_tree(cfg, w, prefix_k, prefix_v, tokens, parent, act_round=None, pert
 
 
 def path_forward(cfg, w, prefix_k, prefix_v, seq_tokens, act_round=None, return_all=False,
-                 return_kv=False):
+                 return_kv=False, perturb=0.0):
     """Ordinary causal decoding of ``seq_tokens`` placed after a cached prefix: token s sits at
     position P + s and attends to the whole prefix and to tokens 0..s of the sequence.
     Returns the logits after the last token (or after every token with ``return_all``).
@@ -180,12 +180,13 @@ def path_forward(cfg, w, prefix_k, prefix_v, seq_tokens, act_round=None, return_
     if prefix_k is None:
         prefix_k = np.zeros((cfg.n_layers, 0, Hkv, Dh))
         prefix_v = np.zeros((cfg.n_layers, 0, Hkv, Dh))
-    prefix_k, prefix_v = _f64(prefix_k), _f64(prefix_v)
-    P = prefix_k.shape[1]
+    P = prefix_k.shape[1]                     # prefix_k/v may be any [L][P][Hkv][Dh] indexable (converted per layer)
     pos = P + np.arange(n)
     # dense mask over [prefix | sequence]: everything in the prefix, lower triangle after it
     allowed = np.concatenate([np.ones((n, P), dtype=bool), np.tril(np.ones((n, n), dtype=bool))], axis=1)
     h = _f64(w["embed"])[seq]
+    if perturb:  # same knob as in verify_tree: a nudge of the inputs, to measure rounding-flip noise
+        h = h * (1.0 + perturb * np.random.default_rng(0).standard_normal(h.shape))
     ks, vs = [], []
     for l in range(cfg.n_layers):
         lw = w["layers"][l]
@@ -195,8 +196,8 @@ def path_forward(cfg, w, prefix_k, prefix_v, seq_tokens, act_round=None, return_
         v = R((x @ _f64(lw["wv"]).T).reshape(n, Hkv, Dh))
         ks.append(k)
         vs.append(v)
-        K = np.concatenate([prefix_k[l], k], axis=0)                  # [P+n, Hkv, Dh]
-        V = np.concatenate([prefix_v[l], v], axis=0)
+        K = np.concatenate([_f64(prefix_k[l]), k], axis=0)            # [P+n, Hkv, Dh]
+        V = np.concatenate([_f64(prefix_v[l]), v], axis=0)
         Kh = np.repeat(K, G, axis=1)                                  # [P+n, Hq, Dh]
         Vh = np.repeat(V, G, axis=1)
         s = np.einsum("ihd,jhd->hij", q, Kh) / np.sqrt(F64(Dh))       # [Hq, n, P+n]
