@@ -78,8 +78,10 @@ def test_c3_four_70b_layers_sampled_paths(sx):
 def test_c5_eighty_layer_model_sampled_path(sx):
     """The benchmark configuration: 2048-node tree, 2048 prefix tokens, all 80 layers (138 GB of
     weights resident).  One root-to-leaf path is re-evaluated by the oracle, streaming a layer at a
-    time.  The bound is the flip-noise budget of an 80-layer bf16 model, far below
-    what any indexing or masking mistake would produce (errors of order 1)."""
+    time.  Measuring the oracle's self-noise floor here as well would double a two-minute test, so
+    the bound is twice the floor measured once on this very path with the same knob (perturb 1e-7:
+    max 0.345; 3e-6: max 0.451; the kernel itself: 0.326; a bf16-activation model against its own
+    fp64-activation arithmetic: 0.79).  Indexing or masking mistakes produce errors of order 5."""
     err, _, rows = _run(sx, "C5", n_paths=1, with_floor=False)
     assert rows >= 10
-    assert err <= 0.25, err
+    assert err <= 2 * 0.345, err
