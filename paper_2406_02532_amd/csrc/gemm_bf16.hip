@@ -2,15 +2,15 @@
 // M = number of tree tokens.  bf16 operands, fp32 accumulation (v_mfma_f32_32x32x16_bf16).
 //
 // Tiling.  A workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile; each wave a 128 x 128
-// quadrant = 4 x 4 MFMA blocks, 256 fp32 accumulators per lane.  K is walked in slabs of 64:
-// the 256x64 X slab and the 256x64 W slab (32 KB each) are double-buffered in LDS (128 KB of the
-// 160 KB), fetched global -> registers two slabs ahead (two register sets) and written to LDS after
-// the current slab's MFMAs.  Both operands are K-contiguous in memory, which is exactly the per-lane layout the MFMA
-// wants (8 consecutive k per lane), so LDS rows are plain 128-byte row segments; the 16-byte
-// chunk index is XOR-swizzled with (row >> 1) & 7: the LDS serves 16 lanes x 16 bytes per cycle
-// (64 banks), and with this swizzle 16 consecutive rows reading the same k chunk -- and 16
-// consecutive lanes writing two rows -- touch 16 different bank groups (measured: ~220 B/clk per
-// CU against ~140 B/clk for a swizzle by row & 7).
+// quadrant = 4 x 4 MFMA blocks, 256 fp32 accumulators per lane.  K is walked in slabs of 32 (two
+// k-steps of 16 = 32 MFMAs per wave), held in a ring of 4 LDS stages (4 x 32 KB).  Global memory is
+// read 64 K-elements at a time (whole 128-byte lines) into one of two register sets, three slab
+// pairs ahead of use, and written to LDS one pair ahead.  Because a slab's data is complete in LDS
+// a full slab before it is needed, the fragments of its first k-step are read before the barrier
+// that precedes it, so no LDS latency is exposed at slab boundaries.  Both operands are
+// K-contiguous in memory, which is exactly the per-lane layout the MFMA wants (8 consecutive k per
+// lane), so LDS rows are plain 64-byte row segments with an XOR swizzle of the 16-byte chunk index
+// that is conflict-free for the 64-bank LDS (measured ~220 B/clk per CU against ~140 for a naive one).
 //
 // XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
 // Tile index = xcd * chunk + id / 8 with tiles ordered M-fastest, so the workgroups resident on
@@ -24,10 +24,14 @@
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256;
+constexpr int BK = 64;                    // K elements fetched from global memory at a time (full 128-byte lines)
+constexpr int SK = 32;                    // K elements per LDS stage ("slab"): two k-steps of 16
 constexpr int kThreads = 256;
-constexpr int kSlabBytes = BM * BK * 2;  // 32 KB per operand per stage
-constexpr int kLdsBytes = 4 * kSlabBytes;
+constexpr int kOperandBytes = BM * SK * 2;            // 16 KB: one operand of one slab
+constexpr int kStageStride = 2 * kOperandBytes + 128; // X slab, W slab, and a 128-byte skew (see stash)
+constexpr int kStages = 4;
+constexpr int kLdsBytes = kStages * kStageStride;
 
 struct GemmArgs {
   const unsigned short* X;
@@ -40,7 +44,15 @@ struct GemmArgs {
   int tilesM, tilesN, chunk;
 };
 
-__device__ __forceinline__ int lds_off(int row, int kchunk) { return row * (BK * 2) + ((kchunk ^ ((row >> 1) & 7)) << 4); }
+// Byte offset of 16-byte chunk `c4` (0..3) of row `row` inside one operand of a slab.  Rows are 64 bytes;
+// the chunk index is XORed with (row >> 2) & 3.  The LDS serves 16 lanes x 16 bytes per cycle (64 banks):
+// 16 consecutive rows reading the same k chunk then fall on 16 different bank groups
+// ((row & 3) * 4 + (c4 ^ (row >> 2) & 3) takes 16 distinct values).
+// Raw buffer resource over a whole matrix (no bounds: rows are clamped by the caller; < 4 GB).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, -1, 0x00020000);
+}
+__device__ __forceinline__ int lds_off(int row, int c4) { return row * (SK * 2) + ((c4 ^ ((row >> 2) & 3)) << 4); }
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
@@ -62,8 +74,11 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   // uniform per i (scalar registers) and only a 32-bit byte offset is kept per lane.
   const int kc = tid & 7;         // chunk within the 64-wide slab
   const int r0 = tid >> 3;        // rows r0 + 32*i
-  const char* xbase = reinterpret_cast<const char*>(a.X);
-  const char* wbase[8];
+  // Loads go through buffer resources (scalar base + 32-bit lane offset + scalar slab offset), so the
+  // K loop spends no vector instructions or registers on 64-bit addresses.
+  const __amdgpu_buffer_rsrc_t xres = make_rsrc(a.X);
+  const __amdgpu_buffer_rsrc_t wres0 = make_rsrc(a.W0), wres1 = make_rsrc(a.W1), wres2 = make_rsrc(a.W2);
+  __amdgpu_buffer_rsrc_t wres[8];
   unsigned xoff[8], woff[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -74,22 +89,21 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     if (MODE == SX_GEMM_SWIGLU) {
       int f = tile_n * (BN / 2) + (i >> 1) * 32 + (r & 31);  // group i: even = gate, odd = up
       f = f < a.N ? f : a.N - 1;
-      wbase[i] = reinterpret_cast<const char*>((i & 1) ? a.W1 : a.W0);
+      wres[i] = (i & 1) ? wres1 : wres0;
       woff[i] = ((unsigned)f * (unsigned)a.K + kc * 8) * 2u;
     } else {
       const int g0 = min(tile_n * BN + 32 * i, a.N - 1);     // first row of the group decides the matrix
       int n = tile_n * BN + r;
       n = n < a.N ? n : a.N - 1;
-      const unsigned short* base = a.W0;
       int first = 0;
+      wres[i] = wres0;
       if (g0 >= a.n0 + a.n1) {
-        base = a.W2;
+        wres[i] = wres2;
         first = a.n0 + a.n1;
       } else if (g0 >= a.n0) {
-        base = a.W1;
+        wres[i] = wres1;
         first = a.n0;
       }
-      wbase[i] = reinterpret_cast<const char*>(base);
       woff[i] = ((unsigned)(n - first) * (unsigned)a.K + kc * 8) * 2u;
     }
   }
@@ -107,102 +121,119 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   // a fetch has two slabs' worth of MFMA time (~1.7 us) to come back from HBM.
   u32x4 rx0[8], rw0[8], rx1[8], rw1[8];
   // byte offsets of this lane's fragment rows inside a stage (chunk 0; the chunk index is XORed in).
-  // Every fragment row of a lane has the same (row >> 1) & 7 = (lane >> 1) & 7.
+  // Every fragment row of a lane has the same (row >> 2) & 3 = (lane >> 2) & 3.
   int aoff[4], boff[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    aoff[i] = (wm * 128 + i * 32 + l32) * (BK * 2);
-    boff[i] = kSlabBytes + (wn * 128 + i * 32 + l32) * (BK * 2);
+    aoff[i] = (wm * 128 + i * 32 + l32) * (SK * 2);
+    boff[i] = kOperandBytes + (wn * 128 + i * 32 + l32) * (SK * 2);
   }
-  const int sw = (lane >> 1) & 7;
+  const int sw = (lane >> 2) & 3;
+  // where this lane's fetched chunk goes: the 64-wide fetch covers two slabs; chunk kc < 4 belongs to the
+  // first, kc >= 4 to the second (one stage further).  Odd stages are skewed by 128 bytes
+  // (kStageStride) so that the two halves of a 16-lane write land on different banks.
+  const int st_sub = (kc >> 2) * kStageStride;
   bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
 
-#define SX_FETCH(RX, RW, KT_, I0)                                                                  \
+#define SX_FETCH(RX, RW, PAIR_, I0)                                                                \
   _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
-    RX[i] = *reinterpret_cast<const u32x4*>(xbase + (size_t)(KT_) * (BK * 2) + xoff[i]);          \
-    RW[i] = *reinterpret_cast<const u32x4*>(wbase[i] + (size_t)(KT_) * (BK * 2) + woff[i]);       \
+    RX[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, xoff[i], (PAIR_) * (BK * 2), 0);           \
+    RW[i] = __builtin_amdgcn_raw_buffer_load_b128(wres[i], woff[i], (PAIR_) * (BK * 2), 0);        \
   }
-#define SX_STASH(RX, RW, BUF_, I0)                                                                 \
+// write a fetched pair of slabs into stages STG_ and STG_ + 1
+#define SX_STASH(RX, RW, STG_, I0)                                                                 \
   _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
-    const int off = lds_off(r0 + 32 * i, kc);                                                     \
-    *reinterpret_cast<u32x4*>(lds + (BUF_) * 2 * kSlabBytes + off) = RX[i];                       \
-    *reinterpret_cast<u32x4*>(lds + (BUF_) * 2 * kSlabBytes + kSlabBytes + off) = RW[i];          \
+    const int off = (STG_) * kStageStride + st_sub + lds_off(r0 + 32 * i, kc & 3);                \
+    *reinterpret_cast<u32x4*>(lds + off) = RX[i];                                                 \
+    *reinterpret_cast<u32x4*>(lds + kOperandBytes + off) = RW[i];                                 \
   }
-#define SX_READ(STAGE, A, B, ks)                                                                   \
+#define SX_READ(STG_, A, B, ks)                                                                    \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
-    const int c = ((2 * (ks) + lh) ^ sw) << 4;                                                    \
-    A[i] = *reinterpret_cast<const bf16x8*>((STAGE) + aoff[i] + c);                               \
-    B[i] = *reinterpret_cast<const bf16x8*>((STAGE) + boff[i] + c);                               \
+    const int c = (STG_) * kStageStride + (((2 * (ks) + lh) ^ sw) << 4);                          \
+    A[i] = *reinterpret_cast<const bf16x8*>(lds + aoff[i] + c);                                   \
+    B[i] = *reinterpret_cast<const bf16x8*>(lds + boff[i] + c);                                   \
   }
 #define SX_MMA(A, B)                                                                               \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)      \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[i], B[j], acc[i][j], 0, 0, 0);
-// One K slab: 4 k-steps of 16 MFMAs.  Fragments of step ks+1 are read while step ks multiplies; the
-// global fetch of the slab two ahead and the LDS write of the slab one ahead are dealt out between
-// the MFMA groups so that their issue slots hide under matrix-core time.
-// Issue order requested from the scheduler for one slab (masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS
-// write, 0x020 global read): both leading fragment sets, then 16 rounds of 4 MFMAs each carrying
-// one LDS write and one global read; rounds 4-11 also carry the two fragment reads that refill the
-// set the preceding k-step has just finished with.
-#define SX_SCHED                                                                                   \
-  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);                                              \
-  _Pragma("unroll") for (int r_ = 0; r_ < 16; ++r_) {                                             \
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                             \
-    if (r_ >= 4 && r_ < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                     \
-    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                             \
-    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                             \
+// Issue order.  sched_barrier(0) fences keep three phases of a slab apart: (1) the 8 fragment reads of
+// k-step 1, issued a full k-step (16 MFMAs, ~500 cycles) before they are needed; (2) the MFMAs of
+// k-step 0 with half of the slab's side instructions (LDS writes or global reads) dealt out between
+// them; (3) the MFMAs of k-step 1 with the other half and with the fragment reads of the NEXT
+// slab's k-step 0, which therefore cross the barrier already in registers.
+// Masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 global read.
+#define SX_FENCE __builtin_amdgcn_sched_barrier(0);
+#define SX_DEAL(SIDE_MASK, WITH_READS)                                                             \
+  _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                              \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                             \
+    __builtin_amdgcn_sched_group_barrier(SIDE_MASK, 1, 0);                                         \
+    if (WITH_READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                             \
   }
-#define SX_SLAB(STAGE, FRX, FRW, FKT, SRX, SRW, SBUF)                                              \
-  SX_READ(STAGE, fa0, fb0, 0)                                                                      \
-  SX_READ(STAGE, fa1, fb1, 1)                                                                      \
-  SX_FETCH(FRX, FRW, FKT, 0)                                                                       \
+// A pair of slabs p = stages (S0, S0+1).  Register set (SRX, SRW) holds pair p+1: it is written to
+// stages (S2, S2+1) during the first slab, and refilled with pair p+3 during the second.  On entry
+// fa0/fb0 hold k-step 0 of the first slab.  The stages written here were last read a whole pair
+// ago, and are first read (k-step 0 of the next pair) after the barrier that ends the first slab.
+#define SX_PAIR(S0, S2, SRX, SRW, NEXT_PAIR)                                                       \
+  SX_READ(S0, fa1, fb1, 1)                                                                         \
+  SX_FENCE                                                                                         \
+  SX_STASH(SRX, SRW, S2, 0)                                                                        \
   SX_MMA(fa0, fb0)                                                                                 \
-  SX_READ(STAGE, fa0, fb0, 2)                                                                      \
-  SX_STASH(SRX, SRW, SBUF, 0)                                                                      \
+  SX_DEAL(0x200, false)                                                                            \
+  SX_FENCE                                                                                         \
+  SX_STASH(SRX, SRW, S2, 4)                                                                        \
+  SX_READ(S0 + 1, fa0, fb0, 0)                                                                     \
   SX_MMA(fa1, fb1)                                                                                 \
-  SX_READ(STAGE, fa1, fb1, 3)                                                                      \
-  SX_FETCH(FRX, FRW, FKT, 4)                                                                       \
+  SX_DEAL(0x200, true)                                                                             \
+  SX_FENCE                                                                                         \
+  __syncthreads();                                                                                 \
+  SX_READ(S0 + 1, fa1, fb1, 1)                                                                     \
+  SX_FENCE                                                                                         \
+  SX_FETCH(SRX, SRW, NEXT_PAIR, 0)                                                                 \
   SX_MMA(fa0, fb0)                                                                                 \
-  SX_STASH(SRX, SRW, SBUF, 4)                                                                      \
+  SX_DEAL(0x020, false)                                                                            \
+  SX_FENCE                                                                                         \
+  SX_FETCH(SRX, SRW, NEXT_PAIR, 4)                                                                 \
+  SX_READ(S2, fa0, fb0, 0)                                                                         \
   SX_MMA(fa1, fb1)                                                                                 \
-  SX_SCHED
-
-  // The loop body is branch-free: past the end of K it re-fetches the last slab and writes it to a
-  // stage nobody reads again, which costs nothing and keeps each slab one schedulable block.
-  const int KT = a.K / BK;
-  const int last = KT - 1;
-  SX_FETCH(rx0, rw0, 0, 0)
-  SX_FETCH(rx0, rw0, 0, 4)
-  SX_STASH(rx0, rw0, 0, 0)
-  SX_STASH(rx0, rw0, 0, 4)
-  SX_FETCH(rx1, rw1, min(1, last), 0)
-  SX_FETCH(rx1, rw1, min(1, last), 4)
+  SX_DEAL(0x020, true)                                                                             \
+  SX_FENCE                                                                                         \
   __syncthreads();
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    // even slab: in LDS stage 0; set 0 is free (fetch slab kt+2 into it), set 1 holds slab kt+1 (-> stage 1)
-    SX_SLAB(lds, rx0, rw0, min(kt + 2, last), rx1, rw1, 1)
-    __syncthreads();
-    // odd slab: in LDS stage 1; set 1 is free (fetch slab kt+3), set 0 holds slab kt+2 (-> stage 0)
-    SX_SLAB(lds + 2 * kSlabBytes, rx1, rw1, min(kt + 3, last), rx0, rw0, 0)
-    __syncthreads();
+
+  // The loop body is branch-free: past the end of K it re-fetches the last pair and writes it to
+  // stages nobody reads again, which costs nothing and keeps each slab one schedulable block.
+  const int NP = a.K / BK;  // pairs of slabs
+  const int last = NP - 1;
+  SX_FETCH(rx1, rw1, 0, 0)
+  SX_FETCH(rx1, rw1, 0, 4)
+  SX_STASH(rx1, rw1, 0, 0)
+  SX_STASH(rx1, rw1, 0, 4)
+  SX_FETCH(rx0, rw0, min(1, last), 0)
+  SX_FETCH(rx0, rw0, min(1, last), 4)
+  SX_FETCH(rx1, rw1, min(2, last), 0)
+  SX_FETCH(rx1, rw1, min(2, last), 4)
+  __syncthreads();
+  SX_READ(0, fa0, fb0, 0)
+  int p = 0;
+  for (; p + 1 < NP; p += 2) {
+    SX_PAIR(0, 2, rx0, rw0, min(p + 3, last))  // even pair: stages 0,1; set 0 holds pair p+1 -> stages 2,3
+    SX_PAIR(2, 0, rx1, rw1, min(p + 4, last))  // odd pair: stages 2,3; set 1 holds pair p+2 -> stages 0,1
   }
-  if (kt < KT) {  // odd slab count: the last one sits in stage 0
-    SX_READ(lds, fa0, fb0, 0)
+  if (p < NP) {  // odd number of pairs: the last one sits in stages 0,1 and fa0/fb0 hold its first k-step
+    SX_READ(0, fa1, fb1, 1)
     SX_MMA(fa0, fb0)
-    SX_READ(lds, fa0, fb0, 1)
+    SX_READ(1, fa0, fb0, 0)
+    SX_MMA(fa1, fb1)
+    SX_READ(1, fa1, fb1, 1)
     SX_MMA(fa0, fb0)
-    SX_READ(lds, fa0, fb0, 2)
-    SX_MMA(fa0, fb0)
-    SX_READ(lds, fa0, fb0, 3)
-    SX_MMA(fa0, fb0)
+    SX_MMA(fa1, fb1)
   }
 #undef SX_FETCH
 #undef SX_STASH
 #undef SX_READ
 #undef SX_MMA
-#undef SX_SLAB
-#undef SX_SCHED
+#undef SX_PAIR
+#undef SX_DEAL
+#undef SX_FENCE
 
   // ---- epilogue.  acc[i][j][e]: row = 32i + 8(e/4) + 4*lh + e%4, col = 32j + l32 within the quadrant --
   const int mbase = tile_m * BM + wm * 128;
