@@ -74,7 +74,8 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
                                                            float* __restrict__ score) {
   constexpr int NW = THREADS / 64;
   __shared__ float smax[THREADS];
-  __shared__ float redf[16];
+  __shared__ float redf[32];
+  __shared__ float s_gmax[64];
   __shared__ int redi[16];
   __shared__ float s_t0;
   __shared__ int s_cnt;
@@ -102,35 +103,44 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
     }
   }
 
-  // ---- log-sum-exp ---------------------------------------------------------------------
+  // ---- maxima: per lane, per group of GS lanes (64 groups), per wave -----------------------------
+  constexpr int GS = THREADS / 64;
   float tm = NEG_INF;
 #pragma unroll
   for (int e = 0; e < IPT4 * 4; ++e) tm = fmaxf(tm, v[e]);
-  smax[tid] = tm;
+  float gm = tm;
+#pragma unroll
+  for (int o = 1; o < GS; o <<= 1) gm = fmaxf(gm, __shfl_xor(gm, o, 64));
+  const float wmx = wave_max(gm);
+  const bool small_k = k <= 64;  // uniform
+  if ((tid & 63) == 0) redf[tid >> 6] = wmx;
+  if ((tid & (GS - 1)) == 0) s_gmax[tid / GS] = gm;
+  if (!small_k) smax[tid] = tm;
   if (tid == 0) s_cnt = 0;
-  const float M = block_max<NW>(tm, redf);
+  __syncthreads();  // (1)
+  float M = redf[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) M = fmaxf(M, redf[w]);
+
+  // ---- sum of exponentials; meanwhile wave 0 ranks the group maxima ---------------------------------
+  // t0 = k-th largest of a set of group maxima (rank by value, then group id) is a lower bound of
+  // the k-th largest entry.  k <= 64: 64 groups ranked by one wave with lane broadcasts (hardly
+  // looser than per-lane maxima and far cheaper); else every lane is a group.
   float se = 0.f;
 #pragma unroll
   for (int e = 0; e < IPT4 * 4; ++e) se += __builtin_amdgcn_exp2f((v[e] - M) * kLog2e);
-  const float S = block_sum<NW>(se, redf);
-  const float lse = M + logf(S);
-
-  // ---- lower bound t0 = k-th largest of a set of group maxima (rank by value, then group id) -----
-  // k <= 64: the lanes are folded into 64 groups and one wave ranks them with lane broadcasts
-  // (hardly looser than per-lane maxima, and ~THREADS/64 times cheaper); else every lane is a group.
-  if (k <= 64) {
+  se = wave_sum(se);
+  if ((tid & 63) == 0) redf[NW + (tid >> 6)] = se;
+  if (small_k) {
     if (tid < 64) {
-      constexpr int GS = THREADS / 64;
-      float gm = smax[tid * GS];
-#pragma unroll
-      for (int j = 1; j < GS; ++j) gm = fmaxf(gm, smax[tid * GS + j]);
+      const float g = s_gmax[tid];
       int rank = 0;
 #pragma unroll
       for (int j = 0; j < 64; ++j) {
-        const float o = __shfl(gm, j, 64);
-        rank += (o > gm || (o == gm && j < tid)) ? 1 : 0;
+        const float o = __shfl(g, j, 64);
+        rank += (o > g || (o == g && j < tid)) ? 1 : 0;
       }
-      if (rank == k - 1) s_t0 = gm;
+      if (rank == k - 1) s_t0 = g;
     }
   } else {
     int rank = 0;
@@ -140,7 +150,11 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
     }
     if (rank == k - 1) s_t0 = tm;
   }
-  __syncthreads();
+  __syncthreads();  // (2)
+  float S = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) S += redf[NW + w];
+  const float lse = M + logf(S);
   const float t0 = s_t0;
 
   // ---- gather candidates >= t0 ---------------------------------------------------------------
@@ -156,19 +170,41 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
       }
     }
   }
-  __syncthreads();
+  __syncthreads();  // (3)
   int C = s_cnt;
-  __syncthreads();
+  const float cl = cum_logp ? cum_logp[row] : 0.f;
 
+  if (small_k && C <= 64) {
+    // ---- the usual case: a few dozen candidates, ordered by one wave in registers -------------------
+    if (tid >= 64) return;
+    unsigned long long x64 = tid < C ? cand[tid] : ~0ull;
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1)
+#pragma unroll
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        const unsigned long long other = __shfl_xor(x64, stride, 64);
+        const bool keep_min = ((tid & stride) == 0) == ((tid & size) == 0);
+        x64 = keep_min ? (x64 < other ? x64 : other) : (x64 < other ? other : x64);
+      }
+    if (tid < k) {
+      const float val = f32_from_order_key(~(unsigned)(x64 >> 32));
+      const float lp = val - lse;
+      const size_t o = row * (size_t)k + tid;
+      topk_idx[o] = (int)(unsigned)(x64 & 0xFFFFFFFFull);
+      topk_logp[o] = lp;
+      if (score) score[o] = cl + lp;
+    }
+    return;
+  }
+  __syncthreads();
   if (C > kCandCap) {  // the bound was useless (massive ties): exact search, re-reading the row from L2
     C = exact_topk_from_memory<THREADS>(x, V, k, redi, &s_cnt, cand);
   }
 
-  // ---- order the candidates and emit the first k -------------------------------------------------
+  // ---- general case: order the candidates in LDS and emit the first k --------------------------------
   const int n = next_pow2(C < 2 ? 2 : C);
   for (int i = C + tid; i < n; i += THREADS) cand[i] = ~0ull;
   block_bitonic_sort_u64<THREADS>(cand, n);
-  const float cl = cum_logp ? cum_logp[row] : 0.f;
   for (int c = tid; c < k; c += THREADS) {
     const unsigned long long e = cand[c];
     const float val = f32_from_order_key(~(unsigned)(e >> 32));
@@ -180,9 +216,9 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
   }
 }
 
-// One workgroup of 512 lanes; lane t owns the flat candidates [t*per, (t+1)*per).
-// REG = true keeps the (<= 128) keys of a lane in registers.
-constexpr int kSelThreads = 512;
+// One workgroup of 1024 lanes; lane t owns the flat candidates [t*per, (t+1)*per).
+// REG = true keeps the (<= 64) keys of a lane in registers.
+constexpr int kSelThreads = 1024;
 
 template <bool REG>
 __global__ __launch_bounds__(kSelThreads) void global_select_kernel(const float* __restrict__ score,
@@ -192,25 +228,31 @@ __global__ __launch_bounds__(kSelThreads) void global_select_kernel(const float*
                                                                     float* __restrict__ out_score,
                                                                     int* __restrict__ n_out) {
   constexpr int NW = kSelThreads / 64;
-  constexpr int RK = 128;  // keys a lane can hold in registers
+  constexpr int RK = 64;  // keys a lane can hold in registers
   extern __shared__ unsigned long long sbuf[];
   __shared__ int redi[16];
   __shared__ int s_wave_ties[NW];
+  __shared__ int s_probe[2][NW];
   __shared__ int s_pos;
 
   const int tid = threadIdx.x;
-  const int lo = tid * per;
-  const int hi = min(n, lo + per);
   const int Bsel = min(B, n);
-  // Order keys; slots past the lane's range hold key 0, below every real key.
+
+  // ---- threshold: K = largest order key with #(key >= K) >= Bsel, by bitwise search --------------------
+  // For the search a lane holds the keys tid, tid + 1024, ... (coalesced); slots past n hold key 0,
+  // below every real key.
   unsigned key[REG ? RK : 1];
   if (REG) {
 #pragma unroll
-    for (int e = 0; e < RK; ++e) key[e] = (lo + e < hi) ? f32_order_key(score[lo + e]) : 0u;
+    for (int e = 0; e < RK; ++e) {
+      const int i = e * kSelThreads + tid;
+      key[e] = i < n ? f32_order_key(score[i]) : 0u;
+    }
   }
-
-  unsigned K = 0;  // largest key with #(key >= K) >= Bsel
+  unsigned K = 0;
   if (n > Bsel) {
+    // One barrier per probe: the per-wave counts alternate between two LDS rows, so the next probe's
+    // writers can never overtake this probe's readers.
     for (int bit = 31; bit >= 0; --bit) {
       const unsigned trial = K | (1u << bit);
       int c = 0;
@@ -218,12 +260,20 @@ __global__ __launch_bounds__(kSelThreads) void global_select_kernel(const float*
 #pragma unroll
         for (int e = 0; e < RK; ++e) c += (key[e] >= trial) ? 1 : 0;
       } else {
-        for (int i = lo; i < hi; ++i) c += (f32_order_key(score[i]) >= trial) ? 1 : 0;
+        for (int i = tid; i < n; i += kSelThreads) c += (f32_order_key(score[i]) >= trial) ? 1 : 0;
       }
-      if (block_sum_i<NW>(c, redi) >= Bsel) K = trial;
+      c = wave_sum_i(c);
+      int* row = s_probe[bit & 1];
+      if ((tid & 63) == 0) row[tid >> 6] = c;
+      __syncthreads();
+      int total = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) total += row[w];
+      if (total >= Bsel) K = trial;
     }
   }
-  // ties: the `need` lowest flat indices among keys == K
+
+  // ---- winners: every key > K, and of the keys == K the `need` lowest flat indices -----------------------
   int gt = 0, eq = 0;
   if (REG) {
 #pragma unroll
@@ -232,47 +282,48 @@ __global__ __launch_bounds__(kSelThreads) void global_select_kernel(const float*
       eq += (key[e] == K) ? 1 : 0;
     }
   } else {
-    for (int i = lo; i < hi; ++i) {
+    for (int i = tid; i < n; i += kSelThreads) {
       const unsigned kk = f32_order_key(score[i]);
       gt += kk > K;
       eq += kk == K;
     }
   }
-  const int need = Bsel - block_sum_i<NW>(gt, redi);
-  int incl = eq;  // inclusive prefix of `eq` over lanes = flat-index order
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o, 64);
-    if ((tid & 63) >= o) incl += t;
-  }
-  if ((tid & 63) == 63) s_wave_ties[tid >> 6] = incl;
   if (tid == 0) s_pos = 0;
-  __syncthreads();
-  int tie_rank = incl - eq;
-  for (int w = 0; w < (tid >> 6); ++w) tie_rank += s_wave_ties[w];
-
+  const int need = Bsel - block_sum_i<NW>(gt, redi);
+  const int ties = block_sum_i<NW>(eq, redi);
   auto push = [&](unsigned kk, int flat) {
     const int pos = atomicAdd(&s_pos, 1);
     sbuf[pos] = ((unsigned long long)(~kk) << 32) | (unsigned)flat;
   };
-  if (REG) {
-#pragma unroll
-    for (int e = 0; e < RK; ++e)
-      if (key[e] > K) push(key[e], lo + e);
-  } else {
-    for (int i = lo; i < hi; ++i) {
-      const unsigned kk = f32_order_key(score[i]);
-      if (kk > K) push(kk, i);
-    }
+  const bool all_ties = (ties == need);  // the usual case (a single key equals K): no ranking needed
+  // (re-read from L2 in a rolled, coalesced loop: pushing from the register copy would unroll 64
+  // conditional atomics and spill)
+#pragma unroll 4
+  for (int i = tid; i < n; i += kSelThreads) {
+    const unsigned kk = f32_order_key(score[i]);
+    if (kk > K || (all_ties && kk == K)) push(kk, i);
   }
-  if (eq > 0 && tie_rank < need) {  // rare: this lane owns some of the ties that make the cut
-    for (int i = lo; i < hi; ++i) {
-      const unsigned kk = f32_order_key(score[i]);
-      if (kk == K) {
-        if (tie_rank < need) push(kk, i);
+  if (!all_ties) {
+    // Rare: more keys equal K than fit.  Lanes walk contiguous ranges so that an exclusive scan of
+    // their tie counts ranks the ties in flat-index order; the `need` first ones are taken.
+    const int lo = min(n, tid * per), hi = min(n, lo + per);
+    int mine = 0;
+    for (int i = lo; i < hi; ++i) mine += f32_order_key(score[i]) == K;
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o, 64);
+      if ((tid & 63) >= o) incl += t;
+    }
+    if ((tid & 63) == 63) s_wave_ties[tid >> 6] = incl;
+    __syncthreads();
+    int tie_rank = incl - mine;
+    for (int w = 0; w < (tid >> 6); ++w) tie_rank += s_wave_ties[w];
+    for (int i = lo; i < hi && tie_rank < need; ++i)
+      if (f32_order_key(score[i]) == K) {
+        push(K, i);
         ++tie_rank;
       }
-    }
   }
   __syncthreads();
   const int nsort = next_pow2(Bsel < 2 ? 2 : Bsel);
@@ -365,7 +416,7 @@ extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_
     configured = true;
   }
   sx_prof_begin(SX_K_SELECT, st);
-  if (per <= 128)
+  if (per <= 64)
     global_select_kernel<true><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
                                                                out_cum_logp, n_out);
   else
