@@ -50,7 +50,7 @@ __device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_
   return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
-__global__ __launch_bounds__(kThreads) void tree_attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char Ks[KTILE * DH * 2];
   __shared__ __attribute__((aligned(16))) char Vt[DH * KTILE * 2];
   const int tid = threadIdx.x;
