@@ -19,6 +19,21 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0
+CAL_COPY_BYTES = 1 << 30
+# HBM bytes per launch of the dominant kernel, from hardware counters (two rocprofv3 --pmc runs of this
+# file, scaled by the calibration copy); the text file states the commands and the arithmetic.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_gateup_swiglu_c5_hbm_traffic.txt")
+
+
+def measured_traffic():
+    """bytes per launch recorded in TRAFFIC_FILE ('traffic_bytes_per_launch = N'), or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -33,6 +48,9 @@ def main():
     ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C5"])
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (development only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB -> 1 GiB device copy after the timed steps, so that a counter run "
+                         "of this command holds a dispatch of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'). "
@@ -55,7 +73,7 @@ def main():
 
     # ---------------- resident inputs -------------------------------------------------------------
     t0 = time.time()
-    w = wl.gen_weights(cfg, seed=1, device=dev, progress=lambda l: (l % 10 == 9) and log(f"  weights: layer {l + 1}/{cfg.n_layers}"))
+    w = wl.gen_weights(cfg, seed=1, device=dev, progress=lambda l: (l % 10 == 9 or cfg.n_layers < 10) and log(f"  weights: layer {l + 1}/{cfg.n_layers}"))
     torch.cuda.synchronize()
     nparam = sum(v.numel() for lw in w["layers"] for v in lw.values()) + w["embed"].numel() + w["lm_head"].numel()
     log(f"weights: {nparam / 1e9:.2f} G parameters ({nparam * 2 / 1e9:.1f} GB) generated on device in {time.time() - t0:.1f}s")
@@ -90,6 +108,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
     assert sx.check_status(ws_v) == 0
+    log(f"warmup: {args.warmup} step(s) done")
 
     launches_per_step = 12 * cfg.n_layers + 16
     sx.profile_enable(launches_per_step * args.steps + 64)
@@ -101,7 +120,15 @@ def main():
     elapsed = time.perf_counter() - t0
     sx.profile_disable()
     records = sx.profile_read(launches_per_step * args.steps + 64)
+    if args.calibration_copy:
+        src = torch.full((CAL_COPY_BYTES // 4,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # the one dispatch with a grid over 2^28 elements that reads and writes CAL_COPY_BYTES each
+        torch.cuda.synchronize()
+        del src, dst
     ms_per_step = elapsed / args.steps * 1e3
+    log(f"timed: {args.steps} step(s) in {elapsed:.3f}s")
     value = T / (elapsed / args.steps)
 
     # ---------------- per-kernel figures -----------------------------------------------------------
@@ -136,7 +163,9 @@ def main():
     dom = "gemm_gateup_swiglu"
     roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<2> (gate|up GEMM + SwiGLU, M=%d N=%d K=%d)" % (T, 2 * F, d),
                     achieved=round(kernels[dom]["tflops"], 3), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 5), traffic=None,
+                    frac=round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 5),
+                    traffic=measured_traffic() if args.workload == "C5" else None,
+                    algorithmic_bytes_per_launch=2.0 * (T * d + 2 * F * d + T * F),
                     flop_per_launch=flops[dom], ms_avg=kernels[dom]["ms_avg"])
 
     out = dict(metric="verified tree tokens/s per target forward (T=%d)" % T, value=round(value, 2), unit="tokens/s",
@@ -162,15 +191,15 @@ def main():
 
 
 def cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p):
-    """The oracle as it stands, on this machine's host cores, on a bounded sample: the first 64 tree
+    """The oracle as it stands, on this machine's host cores, on a bounded sample: the first 320 tree
     nodes (an ancestor-closed sub-tree) through 1 and through 2 layers (+ lm_head) to separate
-    per-layer from per-call cost, 128 rows of the draft expansion, one acceptance walk; scaled to
+    per-layer from per-call cost, 1024 rows of the draft expansion, one acceptance walk; scaled to
     the full step and expressed in the metric's unit."""
     import numpy as np
     import torch
 
     import oracle
-    Ts, Ns = min(64, T), min(128, c4["N"])
+    Ts, Ns = min(320, T), min(1024, c4["N"])
     cpu = lambda t: t.detach().to("cpu")
     log("cpu_baseline: copying 2 layers to the host ...")
     L2 = min(2, cfg.n_layers)

@@ -30,6 +30,8 @@ class _LayersFromDevice:
         self.layers = layers
 
     def __getitem__(self, l):
+        if l % 10 == 9 and len(self.layers) > 10:
+            print(f"    oracle: layer {l + 1}/{len(self.layers)}", flush=True)   # a long run shows its steps
         return {k: v.cpu() for k, v in self.layers[l].items()}
 
 
