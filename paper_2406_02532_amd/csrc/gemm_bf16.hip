@@ -1,16 +1,33 @@
 // Y = X W^T on the gfx950 matrix cores: the linear layers of the decoder forward (Alg. 1, FORWARD) at
-// M = number of tree tokens.  bf16 operands, fp32 accumulation (v_mfma_f32_32x32x16_bf16).
+// M = number of tree tokens.  bf16 operands, fp32 accumulation.
 //
 // Tiling.  A workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile; each wave a 128 x 128
-// quadrant = 4 x 4 MFMA blocks, 256 fp32 accumulators per lane.  K is walked in slabs of 32 (two
-// k-steps of 16 = 32 MFMAs per wave), held in a ring of 4 LDS stages (4 x 32 KB).  Global memory is
-// read 64 K-elements at a time (whole 128-byte lines) into one of two register sets, three slab
-// pairs ahead of use, and written to LDS one pair ahead.  Because a slab's data is complete in LDS
-// a full slab before it is needed, the fragments of its first k-step are read before the barrier
-// that precedes it, so no LDS latency is exposed at slab boundaries.  Both operands are
-// K-contiguous in memory, which is exactly the per-lane layout the MFMA wants (8 consecutive k per
-// lane), so LDS rows are plain 64-byte row segments with an XOR swizzle of the 16-byte chunk index
-// that is conflict-free for the 64-bank LDS (measured ~220 B/clk per CU against ~140 for a naive one).
+// quadrant = 8 x 8 blocks of v_mfma_f32_16x16x32_bf16, 256 fp32 accumulators per lane.  With real
+// operand data the chip is power-limited long before the MFMA issue rate is: in a pure register loop
+// the 16x16x32 shape sustains ~1.95 PFLOP/s against ~1.75 for 32x32x16 (it holds a ~10% higher
+// clock), which is why the smaller block is used.  The product is formed transposed (W rows feed
+// the A operand, X rows the B operand), so a lane ends up with 4 consecutive output columns of one
+// row: 16-byte stores.
+//
+// K is walked in slabs of 32 (one MFMA k-step, 64 MFMAs per wave) held in a ring of 4 LDS stages
+// (4 x 32 KB).
+//
+// Global -> LDS without registers.  Operand slabs are copied by buffer loads that write LDS
+// directly (16 bytes per lane, a wave fills 1 KB of consecutive LDS per instruction), so the K loop
+// spends no vector registers and no LDS-write instructions on staging.  Both operands are
+// K-contiguous in memory, which is the per-lane layout the MFMA wants (8 consecutive k per lane),
+// so an LDS row is a plain 64-byte row segment; the XOR swizzle of its 16-byte chunks that makes
+// fragment reads conflict-free on the 64-bank LDS is applied on the global side (each lane picks
+// the chunk whose swizzled position is the lane's slot in the wave's 1 KB).
+// Each stage is its own __shared__ array: the compiler tracks outstanding loads-to-LDS per array,
+// so a fragment read of one stage does not wait for the copies in flight to the others.
+//
+// Schedule of iteration i (slab i): wait until this wave's copies of slab i+1 have landed,
+// barrier (now everybody's have, and everybody has finished reading slab i, whose fragments were
+// fetched during iteration i-1); start the copies of slab i+4 into the stage slab i occupied;
+// read all fragments of slab i+1 into the second register set while the 64 MFMAs of slab i run.
+// A copy has three iterations to arrive, and the 8 copies of a wave are dealt out evenly between
+// the MFMAs: bursts of copies fill the memory pipeline's queues and stall the wave that issues them.
 //
 // XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
 // Tile index = xcd * chunk + id / 8 with tiles ordered M-fastest, so the workgroups resident on
@@ -18,20 +35,18 @@
 // all of X's row tiles.
 //
 // Epilogues: store fp32, add into an fp32 residual, or SwiGLU.  For SwiGLU the W slab interleaves
-// 32-row groups of W_gate and W_up, so gate and up of one output column sit in the same lane and
+// 16-row groups of W_gate and W_up, so gate and up of one output column sit in the same lane and
 // register of neighbouring accumulator blocks and silu(g)*u needs no data movement.
 #include "kernels.h"
 
 namespace {
 
 constexpr int BM = 256, BN = 256;
-constexpr int BK = 64;                    // K elements fetched from global memory at a time (full 128-byte lines)
-constexpr int SK = 32;                    // K elements per LDS stage ("slab"): two k-steps of 16
+constexpr int BK = 64;                    // K must be a multiple of this (two slabs)
+constexpr int SK = 32;                    // K elements per LDS stage ("slab"): one MFMA k-step
 constexpr int kThreads = 256;
 constexpr int kOperandBytes = BM * SK * 2;            // 16 KB: one operand of one slab
-constexpr int kStageStride = 2 * kOperandBytes + 128; // X slab, W slab, and a 128-byte skew (see stash)
-constexpr int kStages = 4;
-constexpr int kLdsBytes = kStages * kStageStride;
+constexpr int kStageBytes = 2 * kOperandBytes;        // X slab then W slab
 
 struct GemmArgs {
   const unsigned short* X;
@@ -44,23 +59,41 @@ struct GemmArgs {
   int tilesM, tilesN, chunk;
 };
 
-// Byte offset of 16-byte chunk `c4` (0..3) of row `row` inside one operand of a slab.  Rows are 64 bytes;
-// the chunk index is XORed with (row >> 2) & 3.  The LDS serves 16 lanes x 16 bytes per cycle (64 banks):
-// 16 consecutive rows reading the same k chunk then fall on 16 different bank groups
-// ((row & 3) * 4 + (c4 ^ (row >> 2) & 3) takes 16 distinct values).
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
 // Raw buffer resource over a whole matrix (no bounds: rows are clamped by the caller; < 4 GB).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, -1, 0x00020000);
 }
-__device__ __forceinline__ int lds_off(int row, int c4) { return row * (SK * 2) + ((c4 ^ ((row >> 2) & 3)) << 4); }
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]):
+// all LDS reads done, at most N vector-memory operations outstanding.
+constexpr int kWaitVm0 = 0x0070, kWaitVm16 = 0x4070, kWaitVm24 = 0x4078;
+
+// Wait until this wave's LDS reads are done and at most the given number of copies are in flight, then
+// meet the other waves.  The barrier intrinsic alone does not order memory operations for the compiler,
+// and a workgroup fence makes it wait for every copy in flight, so empty asm statements that claim to
+// touch memory pin the LDS reads and the copies to their side of the barrier instead.
+#define SX_WAIT_BARRIER(IMM)              \
+  asm volatile("" ::: "memory");          \
+  __builtin_amdgcn_s_waitcnt(IMM);        \
+  __builtin_amdgcn_s_barrier();           \
+  asm volatile("" ::: "memory");
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
+  // One array per stage (see the header).  Row r of an operand's slab is 64 bytes at r * 64; 16-byte
+  // chunk c of the row sits at position c ^ ((r >> 2) & 3).  The LDS serves 16 lanes x 16 bytes per
+  // cycle (64 banks): 16 consecutive rows reading the same k chunk fall on 16 different bank groups.
+  __shared__ __attribute__((aligned(1024))) unsigned char st0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char st1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char st2[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char st3[kStageBytes];
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const int l32 = lane & 31, lh = lane >> 5;
+  const int l16 = lane & 15, lq = lane >> 4;
 
   // ---- which tile ----------------------------------------------------------------------------
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -68,220 +101,203 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   if (slot >= a.chunk || lin >= a.tilesM * a.tilesN) return;
   const int tile_m = lin % a.tilesM, tile_n = lin / a.tilesM;
 
-  // ---- global source rows of this lane: 8 rows of X and 8 rows of W, one 16-byte chunk each -------
-  // Row r0 + 32 i of the slab.  All lanes of the block share the 32-row group i, and a group never
-  // straddles two weight matrices (segment sizes are multiples of 32), so the matrix base pointer is
-  // uniform per i (scalar registers) and only a 32-bit byte offset is kept per lane.
-  const int kc = tid & 7;         // chunk within the 64-wide slab
-  const int r0 = tid >> 3;        // rows r0 + 32*i
-  // Loads go through buffer resources (scalar base + 32-bit lane offset + scalar slab offset), so the
-  // K loop spends no vector instructions or registers on 64-bit addresses.
+  // ---- global sources of this lane's copies ---------------------------------------------------------
+  // Copy instruction t (0..3) of wave w fills rows 64 w + 16 t .. + 15 of an operand's slab: lane l
+  // supplies row 64 w + 16 t + l / 4, LDS chunk position l % 4, i.e. k chunk (l % 4) ^ ((l >> 4) & 3)
+  // (every row of the instruction has (row >> 2) & 3 = l >> 4).  A 16-row group never straddles two
+  // weight matrices (segment sizes are multiples of 16), so the matrix is uniform per instruction.
+  const int crow = 64 * wave + (lane >> 2);
+  const int cchunk = (lane & 3) ^ lq;
   const __amdgpu_buffer_rsrc_t xres = make_rsrc(a.X);
   const __amdgpu_buffer_rsrc_t wres0 = make_rsrc(a.W0), wres1 = make_rsrc(a.W1), wres2 = make_rsrc(a.W2);
-  __amdgpu_buffer_rsrc_t wres[8];
-  unsigned xoff[8], woff[8];
+  __amdgpu_buffer_rsrc_t wres[4];
+  int xoff[4], woff[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = r0 + 32 * i;
+  for (int t = 0; t < 4; ++t) {
+    const int r = crow + 16 * t;
     int m = tile_m * BM + r;
     m = m < a.M ? m : a.M - 1;
-    xoff[i] = ((unsigned)m * (unsigned)a.K + kc * 8) * 2u;
+    xoff[t] = (int)(((unsigned)m * (unsigned)a.K + cchunk * 8) * 2u);
     if (MODE == SX_GEMM_SWIGLU) {
-      int f = tile_n * (BN / 2) + (i >> 1) * 32 + (r & 31);  // group i: even = gate, odd = up
+      // slab rows in 16-row groups: even group = gate, odd = up; rows 64 w + 16 t are group 4 w + t
+      int f = tile_n * (BN / 2) + (2 * wave + (t >> 1)) * 16 + (lane >> 2);
       f = f < a.N ? f : a.N - 1;
-      wres[i] = (i & 1) ? wres1 : wres0;
-      woff[i] = ((unsigned)f * (unsigned)a.K + kc * 8) * 2u;
+      wres[t] = (t & 1) ? wres1 : wres0;
+      woff[t] = (int)(((unsigned)f * (unsigned)a.K + cchunk * 8) * 2u);
     } else {
-      const int g0 = min(tile_n * BN + 32 * i, a.N - 1);     // first row of the group decides the matrix
+      const int g0 = min(tile_n * BN + 64 * wave + 16 * t, a.N - 1);  // first row of the group decides the matrix
       int n = tile_n * BN + r;
       n = n < a.N ? n : a.N - 1;
       int first = 0;
-      wres[i] = wres0;
+      wres[t] = wres0;
       if (g0 >= a.n0 + a.n1) {
-        wres[i] = wres2;
+        wres[t] = wres2;
         first = a.n0 + a.n1;
       } else if (g0 >= a.n0) {
-        wres[i] = wres1;
+        wres[t] = wres1;
         first = a.n0;
       }
-      woff[i] = ((unsigned)(n - first) * (unsigned)a.K + kc * 8) * 2u;
+      woff[t] = (int)(((unsigned)(n - first) * (unsigned)a.K + cchunk * 8) * 2u);
     }
   }
+  const int cdst = wave * 4096;  // this wave's 4 KB of an operand's slab
 
-  f32x16 acc[4][4];
+  // acc[i][j]: W rows (output columns) 16 i .. + 15 of the quadrant, X rows (output rows) 16 j .. + 15
+  f32x4 acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  // Two register sets stage the global -> LDS traffic two K slabs ahead: the slab fetched during
-  // iteration kt is written to LDS at the end of iteration kt+1 and consumed in iteration kt+2, so
-  // a fetch has two slabs' worth of MFMA time (~1.7 us) to come back from HBM.
-  u32x4 rx0[8], rw0[8], rx1[8], rw1[8];
-  // byte offsets of this lane's fragment rows inside a stage (chunk 0; the chunk index is XORed in).
-  // Every fragment row of a lane has the same (row >> 2) & 3 = (lane >> 2) & 3.
-  int aoff[4], boff[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    aoff[i] = (wm * 128 + i * 32 + l32) * (SK * 2);
-    boff[i] = kOperandBytes + (wn * 128 + i * 32 + l32) * (SK * 2);
-  }
-  const int sw = (lane >> 2) & 3;
-  // where this lane's fetched chunk goes: the 64-wide fetch covers two slabs; chunk kc < 4 belongs to the
-  // first, kc >= 4 to the second (one stage further).  Odd stages are skewed by 128 bytes
-  // (kStageStride) so that the two halves of a 16-lane write land on different banks.
-  const int st_sub = (kc >> 2) * kStageStride;
-  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+  // fragment addresses: row (quadrant base + 16 i + l16), k chunk lq at position lq ^ ((row >> 2) & 3)
+  const int fchunk = (lq ^ ((lane >> 2) & 3)) << 4;
+  const int xrow = (wm * 128 + l16) * (SK * 2) + fchunk;
+  const int wrow = kOperandBytes + (wn * 128 + l16) * (SK * 2) + fchunk;
+  bf16x8 fx0[8], fw0[8], fx1[8], fw1[8];
 
-#define SX_FETCH(RX, RW, PAIR_, I0)                                                                \
-  _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
-    RX[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, xoff[i], (PAIR_) * (BK * 2), 0);           \
-    RW[i] = __builtin_amdgcn_raw_buffer_load_b128(wres[i], woff[i], (PAIR_) * (BK * 2), 0);        \
+// One copy instruction: rows 16 t .. + 15 of this wave's share of X (OP_ 0) or W (OP_ 1) of slab byte
+// offset SO_ into stage STG_.  The K offset travels in the scalar offset: the instruction's immediate
+// offset would be added to the LDS address as well.
+#define SX_COPY1(STG_, SO_, OP_, t)                                                                            \
+  if (OP_)                                                                                                     \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(wres[t], (lds_void_ptr)(STG_ + kOperandBytes + cdst + (t) * 1024), 16,   \
+                                             woff[t], SO_, 0, 0);                                              \
+  else                                                                                                         \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_void_ptr)(STG_ + cdst + (t) * 1024), 16, xoff[t], SO_, 0, 0);
+#define SX_COPY(STG_, SLAB_)                                                                                   \
+  _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                             \
+    SX_COPY1(STG_, (SLAB_) * (SK * 2), 0, t)                                                                   \
+    SX_COPY1(STG_, (SLAB_) * (SK * 2), 1, t)                                                                   \
   }
-// write a fetched pair of slabs into stages STG_ and STG_ + 1
-#define SX_STASH(RX, RW, STG_, I0)                                                                 \
-  _Pragma("unroll") for (int i = I0; i < I0 + 4; ++i) {                                           \
-    const int off = (STG_) * kStageStride + st_sub + lds_off(r0 + 32 * i, kc & 3);                \
-    *reinterpret_cast<u32x4*>(lds + off) = RX[i];                                                 \
-    *reinterpret_cast<u32x4*>(lds + kOperandBytes + off) = RW[i];                                 \
+#define SX_READW(STG_, FW, i) FW[i] = *reinterpret_cast<const bf16x8*>(STG_ + wrow + (i) * (16 * SK * 2));
+#define SX_READX(STG_, FX, i) FX[i] = *reinterpret_cast<const bf16x8*>(STG_ + xrow + (i) * (16 * SK * 2));
+#define SX_READ(STG_, FX, FW)                                                                                  \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) { SX_READW(STG_, FW, i) SX_READX(STG_, FX, i) }
+// The MFMA is written out: left to itself the compiler gives an accumulator that is updated more than
+// once per loop body a new destination register each time and shuffles hundreds of registers per
+// iteration to undo it.  "+a" keeps every accumulator in place in the accumulation registers.  The
+// statements are volatile, so the issue order below is the one written here.
+#define SX_MFMA(ACC, A, B) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(A), "v"(B));
+#define SX_MMA(FX, FW)                                                                                         \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) _Pragma("unroll") for (int j = 0; j < 8; ++j)                  \
+      SX_MFMA(acc[i][j], FW[i], FX[j])
+// Iteration: the slab in the C* registers is multiplied row block by row block; between the MFMAs of
+// row block r go one copy instruction of slab SLAB_ (into STG_F, the stage the current slab was read
+// from) and the reads of row block r of the next slab (from STG_N into the N* registers).
+#define SX_ITER(STG_N, CFX, CFW, NFX, NFW, STG_F, SLAB_)                                                       \
+  SX_WAIT_BARRIER(kWaitVm16)                                                                                   \
+  {                                                                                                            \
+    const int so = (SLAB_) * (SK * 2);                                                                         \
+    _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                                           \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) SX_MFMA(acc[r][j], CFW[r], CFX[j])                         \
+      SX_COPY1(STG_F, so, r & 1, r >> 1)                                                                       \
+      SX_READW(STG_N, NFW, r)                                                                                  \
+      _Pragma("unroll") for (int j = 4; j < 8; ++j) SX_MFMA(acc[r][j], CFW[r], CFX[j])                         \
+      SX_READX(STG_N, NFX, r)                                                                                  \
+    }                                                                                                          \
   }
-#define SX_READ(STG_, A, B, ks)                                                                    \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
-    const int c = (STG_) * kStageStride + (((2 * (ks) + lh) ^ sw) << 4);                          \
-    A[i] = *reinterpret_cast<const bf16x8*>(lds + aoff[i] + c);                                   \
-    B[i] = *reinterpret_cast<const bf16x8*>(lds + boff[i] + c);                                   \
-  }
-#define SX_MMA(A, B)                                                                               \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)      \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[i], B[j], acc[i][j], 0, 0, 0);
-// Issue order.  sched_barrier(0) fences keep three phases of a slab apart: (1) the 8 fragment reads of
-// k-step 1, issued a full k-step (16 MFMAs, ~500 cycles) before they are needed; (2) the MFMAs of
-// k-step 0 with half of the slab's side instructions (LDS writes or global reads) dealt out between
-// them; (3) the MFMAs of k-step 1 with the other half and with the fragment reads of the NEXT
-// slab's k-step 0, which therefore cross the barrier already in registers.
-// Masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 global read.
-#define SX_FENCE __builtin_amdgcn_sched_barrier(0);
-#define SX_DEAL(SIDE_MASK, WITH_READS)                                                             \
-  _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                              \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                             \
-    __builtin_amdgcn_sched_group_barrier(SIDE_MASK, 1, 0);                                         \
-    if (WITH_READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                             \
-  }
-// A pair of slabs p = stages (S0, S0+1).  Register set (SRX, SRW) holds pair p+1: it is written to
-// stages (S2, S2+1) during the first slab, and refilled with pair p+3 during the second.  On entry
-// fa0/fb0 hold k-step 0 of the first slab.  The stages written here were last read a whole pair
-// ago, and are first read (k-step 0 of the next pair) after the barrier that ends the first slab.
-#define SX_PAIR(S0, S2, SRX, SRW, NEXT_PAIR)                                                       \
-  SX_READ(S0, fa1, fb1, 1)                                                                         \
-  SX_FENCE                                                                                         \
-  SX_STASH(SRX, SRW, S2, 0)                                                                        \
-  SX_MMA(fa0, fb0)                                                                                 \
-  SX_DEAL(0x200, false)                                                                            \
-  SX_FENCE                                                                                         \
-  SX_STASH(SRX, SRW, S2, 4)                                                                        \
-  SX_READ(S0 + 1, fa0, fb0, 0)                                                                     \
-  SX_MMA(fa1, fb1)                                                                                 \
-  SX_DEAL(0x200, true)                                                                             \
-  SX_FENCE                                                                                         \
-  __syncthreads();                                                                                 \
-  SX_READ(S0 + 1, fa1, fb1, 1)                                                                     \
-  SX_FENCE                                                                                         \
-  SX_FETCH(SRX, SRW, NEXT_PAIR, 0)                                                                 \
-  SX_MMA(fa0, fb0)                                                                                 \
-  SX_DEAL(0x020, false)                                                                            \
-  SX_FENCE                                                                                         \
-  SX_FETCH(SRX, SRW, NEXT_PAIR, 4)                                                                 \
-  SX_READ(S2, fa0, fb0, 0)                                                                         \
-  SX_MMA(fa1, fb1)                                                                                 \
-  SX_DEAL(0x020, true)                                                                             \
-  SX_FENCE                                                                                         \
-  __syncthreads();
 
-  // The loop body is branch-free: past the end of K it re-fetches the last pair and writes it to
-  // stages nobody reads again, which costs nothing and keeps each slab one schedulable block.
-  const int NP = a.K / BK;  // pairs of slabs
-  const int last = NP - 1;
-  SX_FETCH(rx1, rw1, 0, 0)
-  SX_FETCH(rx1, rw1, 0, 4)
-  SX_STASH(rx1, rw1, 0, 0)
-  SX_STASH(rx1, rw1, 0, 4)
-  SX_FETCH(rx0, rw0, min(1, last), 0)
-  SX_FETCH(rx0, rw0, min(1, last), 4)
-  SX_FETCH(rx1, rw1, min(2, last), 0)
-  SX_FETCH(rx1, rw1, min(2, last), 4)
-  __syncthreads();
-  SX_READ(0, fa0, fb0, 0)
-  int p = 0;
-  for (; p + 1 < NP; p += 2) {
-    SX_PAIR(0, 2, rx0, rw0, min(p + 3, last))  // even pair: stages 0,1; set 0 holds pair p+1 -> stages 2,3
-    SX_PAIR(2, 0, rx1, rw1, min(p + 4, last))  // odd pair: stages 2,3; set 1 holds pair p+2 -> stages 0,1
+  // The loop body is branch-free: past the end of K it copies the last slab again, into stages nobody
+  // reads any more, and reads fragments nobody uses.
+  const int NS = a.K / SK;  // slabs (even)
+  const int last = NS - 1;
+  SX_COPY(st0, 0)
+  SX_COPY(st1, 1)
+  SX_COPY(st2, min(2, last))
+  SX_COPY(st3, min(3, last))
+  SX_WAIT_BARRIER(kWaitVm24)
+  SX_READ(st0, fx0, fw0)
+  int s = 0;
+  for (; s + 4 <= NS; s += 4) {
+    SX_ITER(st1, fx0, fw0, fx1, fw1, st0, min(s + 4, last))
+    SX_ITER(st2, fx1, fw1, fx0, fw0, st1, min(s + 5, last))
+    SX_ITER(st3, fx0, fw0, fx1, fw1, st2, min(s + 6, last))
+    SX_ITER(st0, fx1, fw1, fx0, fw0, st3, min(s + 7, last))
   }
-  if (p < NP) {  // odd number of pairs: the last one sits in stages 0,1 and fa0/fb0 hold its first k-step
-    SX_READ(0, fa1, fb1, 1)
-    SX_MMA(fa0, fb0)
-    SX_READ(1, fa0, fb0, 0)
-    SX_MMA(fa1, fb1)
-    SX_READ(1, fa1, fb1, 1)
-    SX_MMA(fa0, fb0)
-    SX_MMA(fa1, fb1)
+  if (s < NS) {  // two slabs left: they sit in stages 0, 1 and fx0/fw0 hold the first
+    SX_WAIT_BARRIER(kWaitVm0)
+    SX_READ(st1, fx1, fw1)
+    SX_MMA(fx0, fw0)
+    SX_MMA(fx1, fw1)
   }
-#undef SX_FETCH
-#undef SX_STASH
+  // Copies past the end of K may still be in flight: they must land before this workgroup's LDS is released.
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  // the matrix pipe's last results must be written back before ordinary instructions read them; the
+  // compiler cannot see the hand-written MFMAs, so the wait states are spelled out
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#undef SX_COPY1
+#undef SX_COPY
+#undef SX_READW
+#undef SX_READX
 #undef SX_READ
+#undef SX_MFMA
 #undef SX_MMA
-#undef SX_PAIR
-#undef SX_DEAL
-#undef SX_FENCE
+#undef SX_ITER
 
-  // ---- epilogue.  acc[i][j][e]: row = 32i + 8(e/4) + 4*lh + e%4, col = 32j + l32 within the quadrant --
+  // ---- epilogue.  acc[i][j][e]: output row 16 j + l16 of the quadrant, W row 16 i + 4 lq + e ---------
   const int mbase = tile_m * BM + wm * 128;
+  const bool vec = (a.N & 3) == 0;  // then every group of 4 columns is whole and 16-byte (8-byte) aligned
   if (MODE == SX_GEMM_SWIGLU) {
     unsigned short* Y = static_cast<unsigned short*>(a.Y);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 8; ++j) {
+      const int m = mbase + 16 * j + l16;
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const int f = tile_n * (BN / 2) + wn * 64 + jj * 32 + l32;
+      for (int ii = 0; ii < 4; ++ii) {
+        const int f = tile_n * (BN / 2) + wn * 64 + ii * 16 + 4 * lq;
+        if (m >= a.M || f >= a.N) continue;
+        unsigned short h[4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mbase + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-          if (m < a.M && f < a.N) {
-            const float g = acc[i][2 * jj][e], u = acc[i][2 * jj + 1][e];
-            Y[(size_t)m * a.N + f] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
-          }
+        for (int e = 0; e < 4; ++e) {
+          const float g = acc[2 * ii][j][e], u = acc[2 * ii + 1][j][e];
+          h[e] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
+        }
+        unsigned short* y = Y + (size_t)m * a.N + f;
+        if (vec) {
+          u32x2 v;
+          v[0] = h[0] | ((uint32_t)h[1] << 16);
+          v[1] = h[2] | ((uint32_t)h[3] << 16);
+          *reinterpret_cast<u32x2*>(y) = v;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (f + e < a.N) y[e] = h[e];
         }
       }
+    }
   } else {
     float* Y = static_cast<float*>(a.Y);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 8; ++j) {
+      const int m = mbase + 16 * j + l16;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int n = tile_n * BN + wn * 128 + j * 32 + l32;
+      for (int i = 0; i < 8; ++i) {
+        const int n = tile_n * BN + wn * 128 + 16 * i + 4 * lq;
+        if (m >= a.M || n >= a.N) continue;
+        float* y = Y + (size_t)m * a.N + n;
+        if (vec) {
+          f32x4 v = acc[i][j];
+          if (MODE == SX_GEMM_RESIDUAL) v += *reinterpret_cast<const f32x4*>(y);
+          *reinterpret_cast<f32x4*>(y) = v;
+        } else {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mbase + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-          if (m < a.M && n < a.N) {
-            float* y = Y + (size_t)m * a.N + n;
-            if (MODE == SX_GEMM_RESIDUAL) *y += acc[i][j][e];
-            else *y = acc[i][j][e];
-          }
+          for (int e = 0; e < 4; ++e)
+            if (n + e < a.N) {
+              if (MODE == SX_GEMM_RESIDUAL) y[e] += acc[i][j][e];
+              else y[e] = acc[i][j][e];
+            }
         }
       }
+    }
   }
 }
+#undef SX_WAIT_BARRIER
 
 template <int MODE>
 int launch(const GemmArgs& a, hipStream_t st) {
-  static bool configured = false;  // raising the dynamic-LDS cap is a per-kernel, per-process setting
-  if (!configured) {
-    SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    configured = true;
-  }
-  gemm_bf16_kernel<MODE><<<8 * a.chunk, kThreads, kLdsBytes, st>>>(a);
+  gemm_bf16_kernel<MODE><<<8 * a.chunk, kThreads, 0, st>>>(a);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }
@@ -291,6 +307,8 @@ int launch(const GemmArgs& a, hipStream_t st) {
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                         void* Y, int M, int K, int mode, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || n0 < 1) return SX_ERR_SHAPE;
+  // a 16-row copy group must not straddle two stacked weight matrices
+  if (mode != SX_GEMM_SWIGLU && ((n1 > 0 && n0 % 16 != 0) || (n2 > 0 && n1 % 16 != 0))) return SX_ERR_SHAPE;
   GemmArgs a;
   a.X = static_cast<const unsigned short*>(X);
   a.W0 = static_cast<const unsigned short*>(W0);
