@@ -42,10 +42,9 @@
 namespace {
 
 constexpr int BM = 256, BN = 256;
-constexpr int BK = 64;                    // K must be a multiple of this (two slabs)
-constexpr int SK = 32;                    // K elements per LDS stage ("slab"): one MFMA k-step
+constexpr int BK = 64;                    // K elements per LDS stage ("slab"): two MFMA k-steps, whole 128-byte lines
 constexpr int kThreads = 256;
-constexpr int kOperandBytes = BM * SK * 2;            // 16 KB: one operand of one slab
+constexpr int kOperandBytes = BM * BK * 2;            // 32 KB: one operand of one slab
 constexpr int kStageBytes = 2 * kOperandBytes;        // X slab then W slab
 
 struct GemmArgs {
@@ -68,7 +67,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]):
 // all LDS reads done, at most N vector-memory operations outstanding.
-constexpr int kWaitVm0 = 0x0070, kWaitVm16 = 0x4070, kWaitVm24 = 0x4078;
+constexpr int kWaitVm0 = 0x0070, kWaitVm16 = 0x4070;
 
 // Wait until this wave's LDS reads are done and at most the given number of copies are in flight, then
 // meet the other waves.  The barrier intrinsic alone does not order memory operations for the compiler,
@@ -82,13 +81,11 @@ constexpr int kWaitVm0 = 0x0070, kWaitVm16 = 0x4070, kWaitVm24 = 0x4078;
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
-  // One array per stage (see the header).  Row r of an operand's slab is 64 bytes at r * 64; 16-byte
-  // chunk c of the row sits at position c ^ ((r >> 2) & 3).  The LDS serves 16 lanes x 16 bytes per
+  // One array per stage (see the header).  Row r of an operand's slab is 128 bytes at r * 128; 16-byte
+  // chunk c of the row sits at position c ^ ((r >> 1) & 7).  The LDS serves 16 lanes x 16 bytes per
   // cycle (64 banks): 16 consecutive rows reading the same k chunk fall on 16 different bank groups.
-  __shared__ __attribute__((aligned(1024))) unsigned char st0[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char st1[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char st2[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char st3[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char stA[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char stB[kStageBytes];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -102,30 +99,31 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   const int tile_m = lin % a.tilesM, tile_n = lin / a.tilesM;
 
   // ---- global sources of this lane's copies ---------------------------------------------------------
-  // Copy instruction t (0..3) of wave w fills rows 64 w + 16 t .. + 15 of an operand's slab: lane l
-  // supplies row 64 w + 16 t + l / 4, LDS chunk position l % 4, i.e. k chunk (l % 4) ^ ((l >> 4) & 3)
-  // (every row of the instruction has (row >> 2) & 3 = l >> 4).  A 16-row group never straddles two
-  // weight matrices (segment sizes are multiples of 16), so the matrix is uniform per instruction.
-  const int crow = 64 * wave + (lane >> 2);
-  const int cchunk = (lane & 3) ^ lq;
+  // Copy instruction t (0..7) of wave w fills rows 64 w + 8 t .. + 7 of an operand's slab (1 KB of LDS):
+  // lane l supplies row 64 w + 8 t + l / 8, LDS chunk position l % 8, i.e. k chunk
+  // (l % 8) ^ ((row >> 1) & 7) with (row >> 1) & 7 = (4 t + l / 16) & 7.  Eight lanes read one whole
+  // 128-byte line: the L2 serves whole-line requests half again as fast as half-line ones.  An 8-row
+  // group never straddles two weight matrices (segment sizes are multiples of 16).
+  const int crow = 64 * wave + (lane >> 3);
   const __amdgpu_buffer_rsrc_t xres = make_rsrc(a.X);
   const __amdgpu_buffer_rsrc_t wres0 = make_rsrc(a.W0), wres1 = make_rsrc(a.W1), wres2 = make_rsrc(a.W2);
-  __amdgpu_buffer_rsrc_t wres[4];
-  int xoff[4], woff[4];
+  __amdgpu_buffer_rsrc_t wres[8];
+  int xoff[8], woff[8];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int r = crow + 16 * t;
+  for (int t = 0; t < 8; ++t) {
+    const int r = crow + 8 * t;
+    const int cchunk = (lane & 7) ^ ((4 * (t & 1) + (lane >> 4)) & 7);
     int m = tile_m * BM + r;
     m = m < a.M ? m : a.M - 1;
     xoff[t] = (int)(((unsigned)m * (unsigned)a.K + cchunk * 8) * 2u);
     if (MODE == SX_GEMM_SWIGLU) {
-      // slab rows in 16-row groups: even group = gate, odd = up; rows 64 w + 16 t are group 4 w + t
-      int f = tile_n * (BN / 2) + (2 * wave + (t >> 1)) * 16 + (lane >> 2);
+      // slab rows in 16-row groups: even group = gate, odd = up; rows 64 w + 8 t are in group 4 w + t / 2
+      int f = tile_n * (BN / 2) + (2 * wave + (t >> 2)) * 16 + (t & 1) * 8 + (lane >> 3);
       f = f < a.N ? f : a.N - 1;
-      wres[t] = (t & 1) ? wres1 : wres0;
+      wres[t] = (t & 2) ? wres1 : wres0;
       woff[t] = (int)(((unsigned)f * (unsigned)a.K + cchunk * 8) * 2u);
     } else {
-      const int g0 = min(tile_n * BN + 64 * wave + 16 * t, a.N - 1);  // first row of the group decides the matrix
+      const int g0 = min(tile_n * BN + 64 * wave + 8 * t, a.N - 1);  // first row of the group decides the matrix
       int n = tile_n * BN + r;
       n = n < a.N ? n : a.N - 1;
       int first = 0;
@@ -140,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
       woff[t] = (int)(((unsigned)(n - first) * (unsigned)a.K + cchunk * 8) * 2u);
     }
   }
-  const int cdst = wave * 4096;  // this wave's 4 KB of an operand's slab
+  const int cdst = wave * 8192;  // this wave's 8 KB of an operand's slab
 
   // acc[i][j]: W rows (output columns) 16 i .. + 15 of the quadrant, X rows (output rows) 16 j .. + 15
   f32x4 acc[8][8];
@@ -151,14 +149,15 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  // fragment addresses: row (quadrant base + 16 i + l16), k chunk lq at position lq ^ ((row >> 2) & 3)
-  const int fchunk = (lq ^ ((lane >> 2) & 3)) << 4;
-  const int xrow = (wm * 128 + l16) * (SK * 2) + fchunk;
-  const int wrow = kOperandBytes + (wn * 128 + l16) * (SK * 2) + fchunk;
-  bf16x8 fx0[8], fw0[8], fx1[8], fw1[8];
+  // fragment addresses: row (quadrant base + 16 i + l16), k chunk 4 ks + lq at position ^ ((row >> 1) & 7)
+  const int fsw = (l16 >> 1) & 7;
+  const int xrow = (wm * 128 + l16) * (BK * 2);
+  const int wrow = kOperandBytes + (wn * 128 + l16) * (BK * 2);
+  const int kc0 = ((lq ^ fsw) << 4), kc1 = (((4 + lq) ^ fsw) << 4);
+  bf16x8 fx0[8], fw0[8], fx1[8], fw1[8];   // k-step 0 and k-step 1 of a slab
 
-// One copy instruction: rows 16 t .. + 15 of this wave's share of X (OP_ 0) or W (OP_ 1) of slab byte
-// offset SO_ into stage STG_.  The K offset travels in the scalar offset: the instruction's immediate
+// One copy instruction: rows 8 t .. + 7 of this wave's share of X (OP_ 0) or W (OP_ 1) at byte offset SO_
+// along K into stage STG_.  The K offset travels in the scalar offset: the instruction's immediate
 // offset would be added to the LDS address as well.
 #define SX_COPY1(STG_, SO_, OP_, t)                                                                            \
   if (OP_)                                                                                                     \
@@ -167,14 +166,12 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   else                                                                                                         \
     __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_void_ptr)(STG_ + cdst + (t) * 1024), 16, xoff[t], SO_, 0, 0);
 #define SX_COPY(STG_, SLAB_)                                                                                   \
-  _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                             \
-    SX_COPY1(STG_, (SLAB_) * (SK * 2), 0, t)                                                                   \
-    SX_COPY1(STG_, (SLAB_) * (SK * 2), 1, t)                                                                   \
+  _Pragma("unroll") for (int t = 0; t < 8; ++t) {                                                             \
+    SX_COPY1(STG_, (SLAB_) * (BK * 2), 0, t)                                                                   \
+    SX_COPY1(STG_, (SLAB_) * (BK * 2), 1, t)                                                                   \
   }
-#define SX_READW(STG_, FW, i) FW[i] = *reinterpret_cast<const bf16x8*>(STG_ + wrow + (i) * (16 * SK * 2));
-#define SX_READX(STG_, FX, i) FX[i] = *reinterpret_cast<const bf16x8*>(STG_ + xrow + (i) * (16 * SK * 2));
-#define SX_READ(STG_, FX, FW)                                                                                  \
-  _Pragma("unroll") for (int i = 0; i < 8; ++i) { SX_READW(STG_, FW, i) SX_READX(STG_, FX, i) }
+#define SX_READW(STG_, FW, i, KC) FW[i] = *reinterpret_cast<const bf16x8*>(STG_ + wrow + (i) * (16 * BK * 2) + KC);
+#define SX_READX(STG_, FX, i, KC) FX[i] = *reinterpret_cast<const bf16x8*>(STG_ + xrow + (i) * (16 * BK * 2) + KC);
 // The MFMA is written out: left to itself the compiler gives an accumulator that is updated more than
 // once per loop body a new destination register each time and shuffles hundreds of registers per
 // iteration to undo it.  "+a" keeps every accumulator in place in the accumulation registers.  The
@@ -183,44 +180,69 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #define SX_MMA(FX, FW)                                                                                         \
   _Pragma("unroll") for (int i = 0; i < 8; ++i) _Pragma("unroll") for (int j = 0; j < 8; ++j)                  \
       SX_MFMA(acc[i][j], FW[i], FX[j])
-// Iteration: the slab in the C* registers is multiplied row block by row block; between the MFMAs of
-// row block r go one copy instruction of slab SLAB_ (into STG_F, the stage the current slab was read
-// from) and the reads of row block r of the next slab (from STG_N into the N* registers).
-#define SX_ITER(STG_N, CFX, CFW, NFX, NFW, STG_F, SLAB_)                                                       \
-  SX_WAIT_BARRIER(kWaitVm16)                                                                                   \
-  {                                                                                                            \
-    const int so = (SLAB_) * (SK * 2);                                                                         \
-    _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                                           \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) SX_MFMA(acc[r][j], CFW[r], CFX[j])                         \
-      SX_COPY1(STG_F, so, r & 1, r >> 1)                                                                       \
-      SX_READW(STG_N, NFW, r)                                                                                  \
-      _Pragma("unroll") for (int j = 4; j < 8; ++j) SX_MFMA(acc[r][j], CFW[r], CFX[j])                         \
-      SX_READX(STG_N, NFX, r)                                                                                  \
+// The 16 fragment reads of a k-step, dealt over the 8 row blocks of the phase before it in the order
+// the next phase needs them: W block 0 and all X blocks first, then W blocks 1..7.
+#define SX_READS_A(STG_, FX, FW, KC, r)                                                                        \
+  if (r == 0) { SX_READW(STG_, FW, 0, KC) SX_READX(STG_, FX, 0, KC) }                                          \
+  if (r == 1) { SX_READX(STG_, FX, 2, KC) SX_READX(STG_, FX, 3, KC) }                                          \
+  if (r == 2) { SX_READX(STG_, FX, 5, KC) SX_READX(STG_, FX, 6, KC) }                                          \
+  if (r == 3) { SX_READW(STG_, FW, 1, KC) }                                                                    \
+  if (r == 4) { SX_READW(STG_, FW, 3, KC) }                                                                    \
+  if (r == 5) { SX_READW(STG_, FW, 5, KC) }                                                                    \
+  if (r == 6) { SX_READW(STG_, FW, 7, KC) }
+#define SX_READS_B(STG_, FX, FW, KC, r)                                                                        \
+  if (r == 0) { SX_READX(STG_, FX, 1, KC) }                                                                    \
+  if (r == 1) { SX_READX(STG_, FX, 4, KC) }                                                                    \
+  if (r == 2) { SX_READX(STG_, FX, 7, KC) }                                                                    \
+  if (r == 3) { SX_READW(STG_, FW, 2, KC) }                                                                    \
+  if (r == 4) { SX_READW(STG_, FW, 4, KC) }                                                                    \
+  if (r == 5) { SX_READW(STG_, FW, 6, KC) }
+// One slab from stage STG_ (its k-step 0 already in fx0/fw0):
+//   phase 1: the 64 MFMAs of k-step 0, with the fragment reads of k-step 1 between them;
+//   barrier: everybody has read all of STG_, and everybody's copies of the next slab (stage STG_N) are in;
+//   phase 2: the 64 MFMAs of k-step 1, with the copies of the slab after next (K offset SO_) into STG_
+//   and the reads of the next slab's k-step 0 between them.  The copies go out early in the phase
+//   (kCopyRows row blocks): they have until the next barrier, a slab's worth of MFMAs away.
+#define SX_SLAB(STG_, STG_N, SO_)                                                                              \
+  _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                                             \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) SX_MFMA(acc[r][j], fw0[r], fx0[j])                           \
+    SX_READS_A(STG_, fx1, fw1, kc1, r)                                                                         \
+    _Pragma("unroll") for (int j = 4; j < 8; ++j) SX_MFMA(acc[r][j], fw0[r], fx0[j])                           \
+    SX_READS_B(STG_, fx1, fw1, kc1, r)                                                                         \
+  }                                                                                                            \
+  SX_WAIT_BARRIER(kWaitVm0)                                                                                    \
+  _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                                             \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) SX_MFMA(acc[r][j], fw1[r], fx1[j])                           \
+    if (r < kCopyRows) {                                                                                       \
+      _Pragma("unroll") for (int c = 0; c < 8 / kCopyRows; ++c) SX_COPY1(STG_, SO_, 0, r * (8 / kCopyRows) + c) \
     }                                                                                                          \
+    SX_READS_A(STG_N, fx0, fw0, kc0, r)                                                                        \
+    _Pragma("unroll") for (int j = 4; j < 8; ++j) SX_MFMA(acc[r][j], fw1[r], fx1[j])                           \
+    if (r < kCopyRows) {                                                                                       \
+      _Pragma("unroll") for (int c = 0; c < 8 / kCopyRows; ++c) SX_COPY1(STG_, SO_, 1, r * (8 / kCopyRows) + c) \
+    }                                                                                                          \
+    SX_READS_B(STG_N, fx0, fw0, kc0, r)                                                                        \
   }
+#ifndef SX_COPY_ROWS
+#define SX_COPY_ROWS 8
+#endif
+  constexpr int kCopyRows = SX_COPY_ROWS;
 
-  // The loop body is branch-free: past the end of K it copies the last slab again, into stages nobody
+  // The loop body is branch-free: past the end of K it copies the last slab again, into a stage nobody
   // reads any more, and reads fragments nobody uses.
-  const int NS = a.K / SK;  // slabs (even)
-  const int last = NS - 1;
-  SX_COPY(st0, 0)
-  SX_COPY(st1, 1)
-  SX_COPY(st2, min(2, last))
-  SX_COPY(st3, min(3, last))
-  SX_WAIT_BARRIER(kWaitVm24)
-  SX_READ(st0, fx0, fw0)
+  const int NB = a.K / BK;  // slabs
+  const int last = NB - 1;
+  SX_COPY(stA, 0)
+  SX_COPY(stB, min(1, last))
+  SX_WAIT_BARRIER(kWaitVm16)
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) { SX_READW(stA, fw0, i, kc0) SX_READX(stA, fx0, i, kc0) }
   int s = 0;
-  for (; s + 4 <= NS; s += 4) {
-    SX_ITER(st1, fx0, fw0, fx1, fw1, st0, min(s + 4, last))
-    SX_ITER(st2, fx1, fw1, fx0, fw0, st1, min(s + 5, last))
-    SX_ITER(st3, fx0, fw0, fx1, fw1, st2, min(s + 6, last))
-    SX_ITER(st0, fx1, fw1, fx0, fw0, st3, min(s + 7, last))
+  for (; s + 2 <= NB; s += 2) {
+    SX_SLAB(stA, stB, min(s + 2, last) * (BK * 2))
+    SX_SLAB(stB, stA, min(s + 3, last) * (BK * 2))
   }
-  if (s < NS) {  // two slabs left: they sit in stages 0, 1 and fx0/fw0 hold the first
-    SX_WAIT_BARRIER(kWaitVm0)
-    SX_READ(st1, fx1, fw1)
-    SX_MMA(fx0, fw0)
-    SX_MMA(fx1, fw1)
+  if (s < NB) {  // one slab left, in stage A
+    SX_SLAB(stA, stB, last * (BK * 2))
   }
   // Copies past the end of K may still be in flight: they must land before this workgroup's LDS is released.
   __builtin_amdgcn_s_waitcnt(kWaitVm0);
@@ -231,10 +253,11 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #undef SX_COPY
 #undef SX_READW
 #undef SX_READX
-#undef SX_READ
 #undef SX_MFMA
 #undef SX_MMA
-#undef SX_ITER
+#undef SX_SLAB
+#undef SX_READS_A
+#undef SX_READS_B
 
   // ---- epilogue.  acc[i][j][e]: output row 16 j + l16 of the quadrant, W row 16 i + 4 lq + e ---------
   const int mbase = tile_m * BM + wm * 128;
