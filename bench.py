@@ -161,7 +161,7 @@ def main():
     total_flop = cfg.n_layers * (flops["gemm_qkv"] + flops["gemm_o"] + flops["gemm_gateup_swiglu"] + flops["gemm_down"]
                                  + flops["tree_attn"]) + flops["gemm_lmhead"]
     dom = "gemm_gateup_swiglu"
-    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<2> (gate|up GEMM + SwiGLU, M=%d N=%d K=%d)" % (T, 2 * F, d),
+    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<2, true> (gate|up GEMM + SwiGLU, M=%d N=%d K=%d)" % (T, 2 * F, d),
                     achieved=round(kernels[dom]["tflops"], 3), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 5),
                     traffic=measured_traffic() if args.workload == "C5" else None,
