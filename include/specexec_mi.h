@@ -180,6 +180,19 @@ int sx_row_logsoftmax_topk(const float *logits, int32_t N, int32_t V, int32_t k,
 int sx_gemm_bf16(const void *X, const void *W, const void *W2, void *Y, int32_t M, int32_t N,
                  int32_t K, int32_t mode, void *stream);
 
+/* QKV projection of the decoder layer (Alg. 1, FORWARD) with the rotary embedding applied in the
+ * GEMM's epilogue, head_dim 128: q_out device bf16 [T][n_q_heads][128], k_out and v_out device
+ * bf16 [T][n_kv_heads][128]; q and k are rotated by the angle of positions[i] (device int32 [T]:
+ * prefix length + tree depth of node i), half-split pairing (element j with j + 64), v is not.
+ * X device bf16 [T][d_model], Wq bf16 [n_q_heads*128][d_model], Wk, Wv bf16
+ * [n_kv_heads*128][d_model], d_model % 64 == 0.  workspace: device, 16-byte aligned, at least
+ * sx_qkv_rope_workspace(T) bytes (holds the cos/sin table); caller-owned. */
+size_t sx_qkv_rope_workspace(int32_t T);
+int sx_qkv_rope_bf16(const void *X, const void *Wq, const void *Wk, const void *Wv, int32_t T,
+                     int32_t d_model, int32_t n_q_heads, int32_t n_kv_heads,
+                     const int32_t *positions, float rope_base, void *q_out, void *k_out,
+                     void *v_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Tree attention alone (App. D merged mask), bf16: q device bf16 [T][Hq][128], tree K/V
  * [T][Hkv][128], prefix K/V [P][Hkv][128], out device bf16 [T][Hq][128]; n_q_heads/n_kv_heads in {1,2,4,8}.  workspace sized by
  * sx_tree_attention_workspace. */

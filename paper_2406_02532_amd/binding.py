@@ -10,7 +10,7 @@ import torch
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
 EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
-           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
+           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
            "sx_profile_enable", "sx_profile_disable", "sx_profile_read"]
 
 SX_F32, SX_BF16 = 0, 1
@@ -66,6 +66,10 @@ def _load():
     L.sx_row_logsoftmax_topk.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     L.sx_gemm_bf16.restype = C.c_int
     L.sx_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.sx_qkv_rope_workspace.restype = sz
+    L.sx_qkv_rope_workspace.argtypes = [i32]
+    L.sx_qkv_rope_bf16.restype = C.c_int
+    L.sx_qkv_rope_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, f32, vp, vp, vp, vp, sz, vp]
     L.sx_tree_attention_workspace.restype = sz
     L.sx_tree_attention_workspace.argtypes = [i32, i32, i32]
     L.sx_tree_attention_bf16.restype = C.c_int
@@ -215,6 +219,19 @@ def gemm_bf16(X, W, Y, mode: int = 0, W2=None, stream=None):
     N = W.shape[0]
     _check(lib.sx_gemm_bf16(_ptr(X), _ptr(W), _ptr(W2), _ptr(Y), M, N, K, mode, _stream(stream)), "sx_gemm_bf16")
     return Y
+
+
+def qkv_rope_bf16(X, Wq, Wk, Wv, positions, rope_base: float, stream=None):
+    """sx_qkv_rope_bf16: rotated q [T][Hq][128], rotated k and plain v [T][Hkv][128] from X [T][d]."""
+    T, d = X.shape
+    Hq, Hkv = Wq.shape[0] // 128, Wk.shape[0] // 128
+    q = torch.empty((T, Hq, 128), dtype=torch.bfloat16, device=X.device)
+    k = torch.empty((T, Hkv, 128), dtype=torch.bfloat16, device=X.device)
+    v = torch.empty_like(k)
+    ws = _workspace(lib.sx_qkv_rope_workspace(T), X.device)
+    _check(lib.sx_qkv_rope_bf16(_ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), T, d, Hq, Hkv, _ptr(positions), float(rope_base),
+                                _ptr(q), _ptr(k), _ptr(v), _ptr(ws), ws.numel(), _stream(stream)), "sx_qkv_rope_bf16")
+    return q, k, v
 
 
 def tree_attention_bf16(q, k_tree, v_tree, k_prefix, v_prefix, parent_idx, out=None, workspace=None, stream=None):

@@ -45,6 +45,38 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   for (int c = threadIdx.x; c < d; c += 256) st<W>(x, row + c, h[row + c] * r * ld<W>(g, c));
 }
 
+// Same for d = 1024 * VPT and bf16 output: the row is read once, 16 bytes per lane and instruction, and
+// stays in registers between the two passes.
+template <int VPT>
+__global__ __launch_bounds__(256) void rmsnorm_row_in_regs_kernel(const float* __restrict__ h,
+                                                                  const unsigned short* __restrict__ g, float eps,
+                                                                  unsigned short* __restrict__ x) {
+  __shared__ float red[4];
+  constexpr int d = 1024 * VPT;
+  const f32x4* hr = reinterpret_cast<const f32x4*>(h + (size_t)blockIdx.x * d);
+  f32x4 v[VPT];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    v[i] = hr[i * 256 + threadIdx.x];
+    ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+  }
+  ss = block_sum<4>(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  const u32x2* gr = reinterpret_cast<const u32x2*>(g);
+  u32x2* xr = reinterpret_cast<u32x2*>(x + (size_t)blockIdx.x * d);
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const u32x2 gg = gr[i * 256 + threadIdx.x];
+    const float g0 = bf16_bits_to_f32(gg[0] & 0xffffu), g1 = bf16_bits_to_f32(gg[0] >> 16);
+    const float g2 = bf16_bits_to_f32(gg[1] & 0xffffu), g3 = bf16_bits_to_f32(gg[1] >> 16);
+    u32x2 o;
+    o[0] = f32_to_bf16_bits(v[i][0] * r * g0) | (f32_to_bf16_bits(v[i][1] * r * g1) << 16);
+    o[1] = f32_to_bf16_bits(v[i][2] * r * g2) | (f32_to_bf16_bits(v[i][3] * r * g3) << 16);
+    xr[i * 256 + threadIdx.x] = o;
+  }
+}
+
 // Pair (j, j + Dh/2) of every q and k head is rotated by the node's angle; v is copied.
 template <typename W>
 __global__ void rope_split_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs, int T, int Hq, int Hkv,
@@ -102,6 +134,10 @@ int sx_launch_rmsnorm(const float* h, const void* gain, int dtype, int T, int d,
                       hipStream_t s) {
   if (dtype == SX_F32)
     rmsnorm_kernel<float><<<T, 256, 0, s>>>(h, (const float*)gain, d, eps, (float*)x_out);
+  else if (d == 8192)
+    rmsnorm_row_in_regs_kernel<8><<<T, 256, 0, s>>>(h, (const unsigned short*)gain, eps, (unsigned short*)x_out);
+  else if (d == 4096)
+    rmsnorm_row_in_regs_kernel<4><<<T, 256, 0, s>>>(h, (const unsigned short*)gain, eps, (unsigned short*)x_out);
   else
     rmsnorm_kernel<unsigned short><<<T, 256, 0, s>>>(h, (const unsigned short*)gain, d, eps, (unsigned short*)x_out);
   SX_LAUNCH_CHECK();

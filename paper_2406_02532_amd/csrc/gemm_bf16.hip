@@ -61,6 +61,10 @@ struct GemmArgs {
   void* Y;
   int M, N, K;  // N = logical output columns
   int tilesM, tilesN, chunk;
+  // SX_GEMM_QKV_ROPE only: rotary table [M][64] (cos, sin), outputs bf16 [M][hq][128], [M][hkv][128] x 2
+  const float2* cs;
+  unsigned short *q, *k, *v;
+  int hq, hkv;
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -307,7 +311,55 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   // ---- epilogue.  acc[i][j][e]: output row 16 j + l16 of the quadrant, W row 16 i + 4 lq + e ---------
   const int mbase = tile_m * BM + wm * 128;
   const bool vec = (a.N & 3) == 0;  // then every group of 4 columns is whole and 16-byte (8-byte) aligned
-  if (MODE == SX_GEMM_SWIGLU) {
+  if (MODE == SX_GEMM_QKV_ROPE) {
+    // The quadrant's 128 columns are one head (head_dim 128): query head, key head or value head,
+    // the same for the whole wave.  Column 16 i + 4 lq + e and column + 64 (block i + 4, same lane and
+    // register) are the pair the rotary embedding turns by the row's angle (Alg. 1: node at position
+    // P + depth); the values are rounded to bf16 once, after the rotation.
+    const int head = tile_n * 2 + wn;
+    const bool is_v = head >= a.hq + a.hkv;
+    unsigned short* dst = head < a.hq ? a.q : is_v ? a.v : a.k;
+    const int hh = head < a.hq ? head : is_v ? head - a.hq - a.hkv : head - a.hq;
+    const int nh = head < a.hq ? a.hq : a.hkv;
+    if (head < a.hq + 2 * a.hkv) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int m = mbase + 16 * j + l16;
+        if (m >= a.M) continue;
+        unsigned short* y = dst + ((size_t)m * nh + hh) * 128 + 4 * lq;
+        if (is_v) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            u32x2 o;
+            o[0] = f32_to_bf16_bits(acc[i][j][0]) | (f32_to_bf16_bits(acc[i][j][1]) << 16);
+            o[1] = f32_to_bf16_bits(acc[i][j][2]) | (f32_to_bf16_bits(acc[i][j][3]) << 16);
+            *reinterpret_cast<u32x2*>(y + 16 * i) = o;
+          }
+        } else {
+          const f32x4* t4 = reinterpret_cast<const f32x4*>(a.cs + (size_t)m * 64 + 4 * lq);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const f32x4 c01 = t4[8 * i], c23 = t4[8 * i + 1];  // (cos, sin) of pairs 16 i + 4 lq + 0..3
+            const float cs_[4] = {c01[0], c01[2], c23[0], c23[2]}, sn_[4] = {c01[1], c01[3], c23[1], c23[3]};
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float x0 = acc[i][j][e], x1 = acc[i + 4][j][e];
+              lo[e] = f32_to_bf16_bits(x0 * cs_[e] - x1 * sn_[e]);
+              hi[e] = f32_to_bf16_bits(x0 * sn_[e] + x1 * cs_[e]);
+            }
+            u32x2 o;
+            o[0] = lo[0] | (lo[1] << 16);
+            o[1] = lo[2] | (lo[3] << 16);
+            *reinterpret_cast<u32x2*>(y + 16 * i) = o;
+            o[0] = hi[0] | (hi[1] << 16);
+            o[1] = hi[2] | (hi[3] << 16);
+            *reinterpret_cast<u32x2*>(y + 64 + 16 * i) = o;
+          }
+        }
+      }
+    }
+  } else if (MODE == SX_GEMM_SWIGLU) {
     unsigned short* Y = static_cast<unsigned short*>(a.Y);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -407,6 +459,32 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
     case SX_GEMM_SWIGLU: return launch<SX_GEMM_SWIGLU>(a, st);
   }
   return SX_ERR_SHAPE;
+}
+
+int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
+                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, hipStream_t st) {
+  if (M < 1 || K < BK || K % BK != 0 || hq < 1 || hkv < 1) return SX_ERR_SHAPE;
+  GemmArgs a;
+  a.X = static_cast<const unsigned short*>(X);
+  a.W0 = static_cast<const unsigned short*>(Wq);
+  a.W1 = static_cast<const unsigned short*>(Wk);
+  a.W2 = static_cast<const unsigned short*>(Wv);
+  a.n0 = hq * 128;
+  a.n1 = a.n2 = hkv * 128;
+  a.Y = nullptr;
+  a.M = M;
+  a.K = K;
+  a.N = a.n0 + a.n1 + a.n2;
+  a.tilesM = (M + BM - 1) / BM;
+  a.tilesN = (a.N + BN - 1) / BN;
+  a.chunk = (a.tilesM * a.tilesN + 7) / 8;
+  a.cs = rope_cs;
+  a.q = static_cast<unsigned short*>(q);
+  a.k = static_cast<unsigned short*>(k);
+  a.v = static_cast<unsigned short*>(v);
+  a.hq = hq;
+  a.hkv = hkv;
+  return launch<SX_GEMM_QKV_ROPE>(a, st);
 }
 
 extern "C" int sx_gemm_bf16(const void* X, const void* W, const void* W2, void* Y, int32_t M, int32_t N, int32_t K,

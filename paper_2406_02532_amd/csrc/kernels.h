@@ -9,6 +9,8 @@
 int sx_launch_tree_prep(const int32_t* tokens, const int32_t* parent, int T, int V, int P, int head_dim,
                         float rope_base, int32_t* tok_s, int32_t* par_s, int32_t* depth, float2* rope_cs,
                         int32_t* status, hipStream_t st);
+// cs[T][head_dim/2] = (cos, sin) of (P + pos[i]) * base^(-2j/head_dim), evaluated in fp64.
+int sx_launch_rope_table(const int32_t* pos, int T, int P, int head_dim, float rope_base, float2* rope_cs, hipStream_t st);
 // Per query tile of `nodes_per_tile` consecutive nodes: the sorted union of their ancestors
 // (klist[tile][0..kcnt[tile])) and, per node, a bitmask over positions of that list
 // (rowmask[node][w], bit b of word w <=> list position 64w+b is an ancestor-or-self of node).
@@ -33,11 +35,15 @@ int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_
                             int Hkv, int Dh, float* out, hipStream_t st);
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------------
-enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2 };
+enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2, SX_GEMM_QKV_ROPE = 3 };
 // Y = X [W0;W1;W2]^T with n0/n1/n2 rows per segment (modes 0/1, Y fp32 [M][n0+n1+n2]), or
 // Y bf16 [M][n0] = silu(X W0^T) * (X W1^T) (mode 2, n1 == n0, n2 == 0).
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                         void* Y, int M, int K, int mode, hipStream_t st);
+// q, k, v (bf16 [M][hq][128], [M][hkv][128], [M][hkv][128]) = rotary(X [Wq;Wk;Wv]^T): the QKV projection with
+// the split into heads and the rotation by rope_cs[M][64] = (cos, sin) done in the GEMM's epilogue (v unrotated).
+int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
+                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, hipStream_t st);
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
                              const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,

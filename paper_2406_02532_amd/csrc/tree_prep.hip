@@ -109,9 +109,13 @@ int sx_launch_tree_prep(const int32_t* tokens, const int32_t* parent, int T, int
                         int32_t* status, hipStream_t st) {
   tree_prep_kernel<<<1, kPrepThreads, (size_t)T * sizeof(int), st>>>(tokens, parent, T, V, tok_s, par_s, depth, status);
   SX_LAUNCH_CHECK();
+  return sx_launch_rope_table(depth, T, P, head_dim, rope_base, rope_cs, st);
+}
+
+int sx_launch_rope_table(const int32_t* pos, int T, int P, int head_dim, float rope_base, float2* rope_cs, hipStream_t st) {
   const int half = head_dim / 2;
   const int n = T * half;
-  rope_table_kernel<<<(n + 255) / 256, 256, 0, st>>>(depth, T, P, half, log((double)rope_base), rope_cs);
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, st>>>(pos, T, P, half, log((double)rope_base), rope_cs);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

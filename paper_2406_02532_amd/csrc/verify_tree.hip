@@ -144,7 +144,11 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
     const void* pv = P > 0 ? static_cast<const char*>(prefix_v) + pre_layer : nullptr;
 
     SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
-    if (bf) {
+    const bool fused_rope = bf && Dh == 128;  // the GEMM's epilogue rotates and splits into heads
+    if (fused_rope) {
+      SX_TIMED(SX_K_GEMM_QKV,
+               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, L.rope_cs, L.q, tk, tv, T, d, st));
+    } else if (bf) {
       SX_TIMED(SX_K_GEMM_QKV,
                sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
     } else {
@@ -154,7 +158,8 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
       SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wk, L.qkv + Nq, T, Nkv, d, ld, false, st));
       SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wv, L.qkv + Nq + Nkv, T, Nkv, d, ld, false, st));
     }
-    SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
+    if (!fused_rope)
+      SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
     if (bf) {
       SX_TIMED(SX_K_ATTN,
                sx_launch_tree_attn_bf16(L.q, tk, tv, pk, pv, L.klist, L.kcnt, L.rowmask, T, P, Hq, Hkv, L.o, st));
@@ -236,6 +241,21 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
   SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, L.klist, L.kcnt, L.rowmask, st));
   return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, P, n_q_heads,
                                   n_kv_heads, out, st);
+}
+
+extern "C" size_t sx_qkv_rope_workspace(int32_t T) { return T > 0 ? (size_t)T * 64 * sizeof(float2) : 0; }
+
+extern "C" int sx_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int32_t T, int32_t d_model,
+                                int32_t n_q_heads, int32_t n_kv_heads, const int32_t* positions, float rope_base,
+                                void* q_out, void* k_out, void* v_out, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  if (!X || !Wq || !Wk || !Wv || !positions || !q_out || !k_out || !v_out || !workspace) return SX_ERR_NULL;
+  if (T < 1 || d_model < 64 || d_model % 64 != 0 || n_q_heads < 1 || n_kv_heads < 1) return SX_ERR_SHAPE;
+  if (workspace_bytes < sx_qkv_rope_workspace(T) || (reinterpret_cast<uintptr_t>(workspace) & 15)) return SX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  float2* cs = static_cast<float2*>(workspace);
+  SX_TRY(sx_launch_rope_table(positions, T, 0, 128, rope_base, cs, st));
+  return sx_launch_gemm_qkv_rope_bf16(X, Wq, Wk, Wv, n_q_heads, n_kv_heads, cs, q_out, k_out, v_out, T, d_model, st);
 }
 
 extern "C" int sx_check_status(const void* workspace, void* stream) {

@@ -185,6 +185,27 @@ def test_gemm_bf16_swiglu(sx, M, F, K):
     assert np.all(np.abs(got - ref) <= 0.51 * bf16_ulp(ref) + 1e-5 * np.abs(ref).max())   # correctly rounded up to fp32 noise
 
 
+@pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2)])
+def test_qkv_projection_with_rotary_epilogue(sx, T, d, Hq, Hkv):
+    """The QKV GEMM that rotates and splits into heads in its epilogue, against the oracle's rope applied to
+    fp64 projections (rows beyond a tile, GQA, head columns that cross tile boundaries)."""
+    X = wl.hash_normal(11, (T, d), dtype=torch.bfloat16)
+    Wq = wl.hash_normal(12, (Hq * 128, d), std=0.05, dtype=torch.bfloat16)
+    Wk = wl.hash_normal(13, (Hkv * 128, d), std=0.05, dtype=torch.bfloat16)
+    Wv = wl.hash_normal(14, (Hkv * 128, d), std=0.05, dtype=torch.bfloat16)
+    pos = (np.arange(T) * 7 % 3000 + 5).astype(np.int32)                       # positions up to a few thousand
+    x64 = X.double().numpy()
+    ref_q = oracle.rope((x64 @ Wq.double().numpy().T).reshape(T, Hq, 128), pos, 10000.0)
+    ref_k = oracle.rope((x64 @ Wk.double().numpy().T).reshape(T, Hkv, 128), pos, 10000.0)
+    ref_v = (x64 @ Wv.double().numpy().T).reshape(T, Hkv, 128)
+    q, k, v = sx.qkv_rope_bf16(X.to(dev()), Wq.to(dev()), Wk.to(dev()), Wv.to(dev()), torch.from_numpy(pos).to(dev()), 10000.0)
+    torch.cuda.synchronize()
+    for got, ref in ((q, ref_q), (k, ref_k), (v, ref_v)):
+        got = got.cpu().double().numpy()
+        # correctly rounded to bf16 up to fp32 accumulation / table noise
+        assert np.all(np.abs(got - ref) <= 0.51 * bf16_ulp(ref) + 2e-5 * np.abs(ref).max())
+
+
 def _attn_case(sx, T, P, Hq, Hkv, tree, seed):
     tok, par = tree
     q = wl.hash_normal(seed, (T, Hq, 128), std=1.5, dtype=torch.bfloat16)
