@@ -185,9 +185,11 @@ int sx_gemm_bf16(const void *X, const void *W, const void *W2, void *Y, int32_t 
  * bf16 [T][n_kv_heads][128]; q and k are rotated by the angle of positions[i] (device int32 [T]:
  * prefix length + tree depth of node i), half-split pairing (element j with j + 64), v is not.
  * X device bf16 [T][d_model], Wq bf16 [n_q_heads*128][d_model], Wk, Wv bf16
- * [n_kv_heads*128][d_model], d_model % 64 == 0.  workspace: device, 16-byte aligned, at least
- * sx_qkv_rope_workspace(T) bytes (holds the cos/sin table); caller-owned. */
-size_t sx_qkv_rope_workspace(int32_t T);
+ * [n_kv_heads*128][d_model], d_model % 64 == 0.  workspace: device, 256-byte aligned, at least
+ * sx_qkv_rope_workspace(T, n_q_heads, n_kv_heads) bytes (the cos/sin table and, where the output
+ * tiles fill the chip unevenly, partial sums of the tiles that are cut along K); caller-owned,
+ * contents need not be initialised. */
+size_t sx_qkv_rope_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads);
 int sx_qkv_rope_bf16(const void *X, const void *Wq, const void *Wk, const void *Wv, int32_t T,
                      int32_t d_model, int32_t n_q_heads, int32_t n_kv_heads,
                      const int32_t *positions, float rope_base, void *q_out, void *k_out,

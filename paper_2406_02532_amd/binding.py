@@ -67,7 +67,7 @@ def _load():
     L.sx_gemm_bf16.restype = C.c_int
     L.sx_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
     L.sx_qkv_rope_workspace.restype = sz
-    L.sx_qkv_rope_workspace.argtypes = [i32]
+    L.sx_qkv_rope_workspace.argtypes = [i32, i32, i32]
     L.sx_qkv_rope_bf16.restype = C.c_int
     L.sx_qkv_rope_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, f32, vp, vp, vp, vp, sz, vp]
     L.sx_tree_attention_workspace.restype = sz
@@ -228,7 +228,7 @@ def qkv_rope_bf16(X, Wq, Wk, Wv, positions, rope_base: float, stream=None):
     q = torch.empty((T, Hq, 128), dtype=torch.bfloat16, device=X.device)
     k = torch.empty((T, Hkv, 128), dtype=torch.bfloat16, device=X.device)
     v = torch.empty_like(k)
-    ws = _workspace(lib.sx_qkv_rope_workspace(T), X.device)
+    ws = _workspace(lib.sx_qkv_rope_workspace(T, Hq, Hkv), X.device)
     _check(lib.sx_qkv_rope_bf16(_ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), T, d, Hq, Hkv, _ptr(positions), float(rope_base),
                                 _ptr(q), _ptr(k), _ptr(v), _ptr(ws), ws.numel(), _stream(stream)), "sx_qkv_rope_bf16")
     return q, k, v

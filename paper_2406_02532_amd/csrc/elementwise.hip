@@ -119,6 +119,11 @@ __global__ void swiglu_f32_kernel(const float* __restrict__ g, const float* __re
   }
 }
 
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 }  // namespace
 
 int sx_launch_embed(const void* embed, int dtype, const int32_t* tok_s, int T, int d, float* h, hipStream_t s) {
@@ -153,6 +158,12 @@ int sx_launch_rope_split(const float* qkv, const float2* rope_cs, int T, int Hq,
   else
     rope_split_kernel<unsigned short><<<blocks, 256, 0, s>>>(qkv, rope_cs, T, Hq, Hkv, Dh, (unsigned short*)q,
                                                              (unsigned short*)k, (unsigned short*)v);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_zero_i32(int32_t* p, int n, hipStream_t s) {
+  zero_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, n);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

@@ -65,6 +65,10 @@ struct GemmArgs {
   const float2* cs;
   unsigned short *q, *k, *v;
   int hq, hkv;
+  // K split of the tail tiles (split > 1): partial sums [tail tile][split][wave][block][lane] f32x4, counters
+  float* part;
+  int* part_cnt;
+  int split, full_tiles, tail_items, full_per_xcd, tail_per_xcd;
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -102,9 +106,26 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   const int l16 = lane & 15, lq = lane >> 4;
 
   // ---- which tile ----------------------------------------------------------------------------
+  // Without a K split: tile lin = xcd * chunk + slot.  With one (a.split > 1) the first full_per_xcd
+  // slots of an XCD are whole tiles and the rest are the tail: the last few tiles, which would
+  // otherwise occupy a fraction of the chip for a whole round, each cut into a.split K ranges.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int lin = xcd * a.chunk + slot;
-  if (slot >= a.chunk || lin >= a.tilesM * a.tilesN) return;
+  int lin, kpart = 0, ksplit = 1;
+  if (a.split > 1) {
+    if (slot < a.full_per_xcd) {
+      lin = xcd * a.full_per_xcd + slot;
+      if (lin >= a.full_tiles) return;
+    } else {
+      const int idx = xcd * a.tail_per_xcd + (slot - a.full_per_xcd);
+      if (slot - a.full_per_xcd >= a.tail_per_xcd || idx >= a.tail_items) return;
+      lin = a.full_tiles + idx / a.split;
+      kpart = idx % a.split;
+      ksplit = a.split;
+    }
+  } else {
+    lin = xcd * a.chunk + slot;
+    if (slot >= a.chunk || lin >= a.tilesM * a.tilesN) return;
+  }
   const int tile_m = lin % a.tilesM, tile_n = lin / a.tilesM;
 
   // ---- global sources of this lane's copies ---------------------------------------------------------
@@ -278,16 +299,16 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 
   // The loop body is branch-free: past the end of K it copies the last slab again, into a stage nobody
   // reads any more, and reads fragments nobody uses.
-  const int NB = a.K / BK;  // slabs
-  const int last = NB - 1;
-  SX_COPY(stA, 0)
-  SX_COPY(stB, min(1, last))
+  const int NB = a.K / BK / ksplit;          // slabs of this workgroup
+  const int first = kpart * NB, last = first + NB - 1;
+  SX_COPY(stA, first)
+  SX_COPY(stB, min(first + 1, last))
   SX_WAIT_BARRIER(kWaitVm16)
   _Pragma("unroll") for (int i = 0; i < 8; ++i) { SX_READW(stA, fw0, i, kc0) SX_READX(stA, fx0, i, kc0) }
   int s = 0;
   for (; s + 2 <= NB; s += 2) {
-    SX_SLAB(stA, stB, min(s + 2, last) * (BK * 2))
-    SX_SLAB(stB, stA, min(s + 3, last) * (BK * 2))
+    SX_SLAB(stA, stB, min(first + s + 2, last) * (BK * 2))
+    SX_SLAB(stB, stA, min(first + s + 3, last) * (BK * 2))
   }
   if (s < NB) {  // one slab left, in stage A
     SX_SLAB(stA, stB, last * (BK * 2))
@@ -307,6 +328,52 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #undef SX_SLAB
 #undef SX_READS_A
 #undef SX_READS_B
+
+  // ---- K-split tail: the partial sums meet in memory, the last workgroup to arrive adds them up ---------
+  // Every part writes its accumulators (register layout, 1 KB per wave and block: coalesced) and
+  // bumps the tile's counter; whoever finds the others' bumps already there reads all parts back in
+  // part order, so the sum does not depend on who came last.  Nobody waits for anybody.
+  // Coherence without flushing caches: the partial sums are stored and loaded with device scope
+  // (sc1: the stores write through the XCD's L2, the loads do not trust it), the stores are
+  // complete (vmcnt 0) before the counter's device-scope atomic is issued, and the loads are issued
+  // after it has returned.  A release/acquire fence pair would do the same by writing back and
+  // invalidating the whole L2 under the feet of the workgroups still computing (measured: +40 us).
+  if (ksplit > 1) {
+    constexpr int kScopeDevice = 16;  // cache-policy bit sc1
+    __shared__ int s_last;
+    const int tail_tile = lin - a.full_tiles;
+    const __amdgpu_buffer_rsrc_t pres = make_rsrc(a.part);
+    const unsigned mine = (unsigned)(((tail_tile * ksplit + kpart) * 4 + wave) * (64 * 256) + lane * 4) * 4u;  // bytes
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[i][j]), pres, mine + (i * 8 + j) * 1024, 0,
+                                               kScopeDevice);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();
+    if (tid == 0) {
+      const int before = atomicAdd(a.part_cnt + tail_tile, 1);
+      s_last = before == ksplit - 1;
+      if (s_last) a.part_cnt[tail_tile] = 0;  // ready for the next launch
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const unsigned all = (unsigned)((tail_tile * ksplit * 4 + wave) * (64 * 256) + lane * 4) * 4u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        f32x4 sum = __builtin_bit_cast(
+            f32x4, __builtin_amdgcn_raw_buffer_load_b128(pres, all + (i * 8 + j) * 1024, 0, kScopeDevice));
+        for (int p = 1; p < ksplit; ++p)
+          sum += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                               pres, all + (unsigned)p * (4u * 64 * 256 * 4) + (i * 8 + j) * 1024, 0,
+                                               kScopeDevice));
+        acc[i][j] = sum;
+      }
+  }
 
   // ---- epilogue.  acc[i][j][e]: output row 16 j + l16 of the quadrant, W row 16 i + 4 lq + e ---------
   const int mbase = tile_m * BM + wm * 128;
@@ -415,12 +482,49 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 }
 #undef SX_WAIT_BARRIER
 
+int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+  }
+  return n;
+}
+
+// Decides whether the last tiles get a K split: only when they would fill at most half of the chip for
+// a whole round, the caller gave memory for the partial sums, and every part keeps at least 8 slabs.
+void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
+  a.split = 1;
+  a.part = nullptr;
+  a.part_cnt = nullptr;
+  a.full_tiles = a.tail_items = a.full_per_xcd = a.tail_per_xcd = 0;
+  const int cus = compute_units(), tiles = a.tilesM * a.tilesN, nb = a.K / BK;
+  if (!split_ws || tiles <= cus) return;
+  const int rest = tiles % cus;
+  if (rest == 0 || 2 * rest > cus) return;
+  int split = cus / rest;
+  if (split > 4) split = 4;
+  while (split > 1 && (nb % split != 0 || nb / split < 8)) --split;
+  if (split < 2) return;
+  if (split_ws_bytes < sx_gemm_split_workspace(a.M, a.N)) return;
+  a.split = split;
+  a.full_tiles = tiles - rest;
+  a.tail_items = rest * split;
+  a.full_per_xcd = (a.full_tiles + 7) / 8;
+  a.tail_per_xcd = (a.tail_items + 7) / 8;
+  a.part_cnt = static_cast<int*>(split_ws);
+  a.part = reinterpret_cast<float*>(static_cast<char*>(split_ws) + 1024);
+}
+
 template <int MODE>
 int launch(const GemmArgs& a, hipStream_t st) {
+  const int grid = a.split > 1 ? 8 * (a.full_per_xcd + a.tail_per_xcd) : 8 * a.chunk;
   if (a.tilesM == 8 && a.tilesN % 4 == 0)
-    gemm_bf16_kernel<MODE, true><<<8 * a.chunk, kThreads, 0, st>>>(a);
+    gemm_bf16_kernel<MODE, true><<<grid, kThreads, 0, st>>>(a);
   else
-    gemm_bf16_kernel<MODE, false><<<8 * a.chunk, kThreads, 0, st>>>(a);
+    gemm_bf16_kernel<MODE, false><<<grid, kThreads, 0, st>>>(a);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }
@@ -453,6 +557,7 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
     a.tilesN = (a.N + BN - 1) / BN;
   }
   a.chunk = (a.tilesM * a.tilesN + 7) / 8;
+  plan_split(a, nullptr, 0);
   switch (mode) {
     case SX_GEMM_STORE: return launch<SX_GEMM_STORE>(a, st);
     case SX_GEMM_RESIDUAL: return launch<SX_GEMM_RESIDUAL>(a, st);
@@ -461,8 +566,17 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
   return SX_ERR_SHAPE;
 }
 
+// 1 KB of counters (at most 128 tail tiles, zero before the first launch) and up to one partial tile per
+// compute unit (fewer than 256 of them are counted on).
+size_t sx_gemm_split_workspace(int M, int N) {
+  const size_t tiles = (size_t)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const size_t parts = tiles < 512 ? tiles : 512;
+  return 1024 + parts * (size_t)BM * BN * sizeof(float);
+}
+
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
-                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, hipStream_t st) {
+                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
+                                 size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || hq < 1 || hkv < 1) return SX_ERR_SHAPE;
   GemmArgs a;
   a.X = static_cast<const unsigned short*>(X);
@@ -484,6 +598,7 @@ int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, 
   a.v = static_cast<unsigned short*>(v);
   a.hq = hq;
   a.hkv = hkv;
+  plan_split(a, split_ws, split_ws_bytes);
   return launch<SX_GEMM_QKV_ROPE>(a, st);
 }
 

@@ -42,8 +42,14 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
                         void* Y, int M, int K, int mode, hipStream_t st);
 // q, k, v (bf16 [M][hq][128], [M][hkv][128], [M][hkv][128]) = rotary(X [Wq;Wk;Wv]^T): the QKV projection with
 // the split into heads and the rotation by rope_cs[M][64] = (cos, sin) done in the GEMM's epilogue (v unrotated).
+// split_ws (may be null: then no split): sx_gemm_split_workspace(M, N) bytes whose first 1 KB is zero before the first
+// launch (the kernel leaves it zero); lets the last tiles of a launch that fills the chip unevenly be cut along K.
+size_t sx_gemm_split_workspace(int M, int N);
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
-                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, hipStream_t st);
+                                 const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
+                                 size_t split_ws_bytes, hipStream_t st);
+// n int32 zeros (a fill kernel: safe to capture in a graph, unlike a memset node)
+int sx_launch_zero_i32(int32_t* p, int n, hipStream_t st);
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
                              const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,

@@ -26,6 +26,7 @@ struct Layout {
   unsigned long long* rowmask;
   float *h, *qkv, *gate, *up;
   void *x, *q, *o, *act, *tk, *tv;
+  size_t qkv_bytes;
   size_t bytes;
 };
 
@@ -42,7 +43,13 @@ Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
   L.rope_cs = cv.take<float2>((size_t)T * (c.head_dim / 2));
   L.h = cv.take<float>((size_t)T * c.d_model);
   L.x = cv.take<char>((size_t)T * c.d_model * es);
-  L.qkv = cv.take<float>((size_t)T * (Nq + 2 * Nkv));
+  // fp32 QKV for the unfused paths; the fused bf16 path (head_dim 128) keeps its K-split partial sums here
+  {
+    const size_t plain = (size_t)T * (Nq + 2 * Nkv) * sizeof(float);
+    const size_t split = sx_gemm_split_workspace(T, (int)(Nq + 2 * Nkv));
+    L.qkv_bytes = plain > split ? plain : split;
+    L.qkv = reinterpret_cast<float*>(cv.take<char>(L.qkv_bytes));
+  }
   L.q = cv.take<char>((size_t)T * Nq * es);
   L.tk = cv.take<char>((size_t)T * Nkv * es);
   L.tv = cv.take<char>((size_t)T * Nkv * es);
@@ -134,6 +141,7 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
     SX_TIMED(SX_K_PREP,
              sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), L.klist, L.kcnt, L.rowmask, st));
   SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s, T, d, L.h, st));
+  if (bf && Dh == 128) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(L.qkv), 256, st));  // K-split counters
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
@@ -147,7 +155,8 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
     const bool fused_rope = bf && Dh == 128;  // the GEMM's epilogue rotates and splits into heads
     if (fused_rope) {
       SX_TIMED(SX_K_GEMM_QKV,
-               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, L.rope_cs, L.q, tk, tv, T, d, st));
+               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, L.rope_cs, L.q, tk, tv, T, d, L.qkv,
+                                            L.qkv_bytes, st));
     } else if (bf) {
       SX_TIMED(SX_K_GEMM_QKV,
                sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
@@ -243,7 +252,12 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
                                   n_kv_heads, out, st);
 }
 
-extern "C" size_t sx_qkv_rope_workspace(int32_t T) { return T > 0 ? (size_t)T * 64 * sizeof(float2) : 0; }
+// cos/sin table, then (256-byte aligned) the K-split counters and partial sums of the GEMM
+static size_t qkv_rope_table_bytes(int32_t T) { return (((size_t)T * 64 * sizeof(float2)) + 255) & ~(size_t)255; }
+extern "C" size_t sx_qkv_rope_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads) {
+  if (T < 1 || n_q_heads < 1 || n_kv_heads < 1) return 0;
+  return qkv_rope_table_bytes(T) + sx_gemm_split_workspace(T, (n_q_heads + 2 * n_kv_heads) * 128);
+}
 
 extern "C" int sx_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int32_t T, int32_t d_model,
                                 int32_t n_q_heads, int32_t n_kv_heads, const int32_t* positions, float rope_base,
@@ -251,11 +265,15 @@ extern "C" int sx_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, c
                                 void* stream) {
   if (!X || !Wq || !Wk || !Wv || !positions || !q_out || !k_out || !v_out || !workspace) return SX_ERR_NULL;
   if (T < 1 || d_model < 64 || d_model % 64 != 0 || n_q_heads < 1 || n_kv_heads < 1) return SX_ERR_SHAPE;
-  if (workspace_bytes < sx_qkv_rope_workspace(T) || (reinterpret_cast<uintptr_t>(workspace) & 15)) return SX_ERR_WORKSPACE;
+  if (workspace_bytes < sx_qkv_rope_workspace(T, n_q_heads, n_kv_heads) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return SX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   float2* cs = static_cast<float2*>(workspace);
+  char* split_ws = static_cast<char*>(workspace) + qkv_rope_table_bytes(T);
   SX_TRY(sx_launch_rope_table(positions, T, 0, 128, rope_base, cs, st));
-  return sx_launch_gemm_qkv_rope_bf16(X, Wq, Wk, Wv, n_q_heads, n_kv_heads, cs, q_out, k_out, v_out, T, d_model, st);
+  SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(split_ws), 256, st));
+  return sx_launch_gemm_qkv_rope_bf16(X, Wq, Wk, Wv, n_q_heads, n_kv_heads, cs, q_out, k_out, v_out, T, d_model, split_ws,
+                                      workspace_bytes - qkv_rope_table_bytes(T), st);
 }
 
 extern "C" int sx_check_status(const void* workspace, void* stream) {

@@ -185,7 +185,10 @@ def test_gemm_bf16_swiglu(sx, M, F, K):
     assert np.all(np.abs(got - ref) <= 0.51 * bf16_ulp(ref) + 1e-5 * np.abs(ref).max())   # correctly rounded up to fp32 noise
 
 
-@pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2)])
+# the last three shapes give more output tiles than the chip has compute units with a small remainder: the
+# remainder tiles are cut along K (4, 4 and 2 ways) and their partial sums added up by the last workgroup to arrive
+@pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2),
+                                        (2048, 2048, 64, 8), (2048, 2048, 64, 1), (2304, 1024, 64, 8)])
 def test_qkv_projection_with_rotary_epilogue(sx, T, d, Hq, Hkv):
     """The QKV GEMM that rotates and splits into heads in its epilogue, against the oracle's rope applied to
     fp64 projections (rows beyond a tile, GQA, head columns that cross tile boundaries)."""
@@ -246,19 +249,24 @@ def _bf16_model_parity(sx, cfg, P, T, k, seed):
     ref = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16")
     got, tk, tv = _gpu_verify(sx, cfg, w, pk, pv, tok, par, want_kv=True)
     err = float(np.abs(got - ref["logits"]).max())
+    # Noise floor: the oracle against itself with inputs nudged by 3e-6 (the size of fp32-vs-fp64
+    # arithmetic differences).  Rounding flips cascade through the bf16 stages, so two equally
+    # valid bf16 evaluations of one model differ by this much however they are implemented.
+    floor_run = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16", perturb=3e-6)
+    floor = floor_run["logits"]
     # layer 0 sees identical inputs on both sides: its K/V may differ by one bf16 rounding step only
-    # (two where the reference sits just below a power of two); deeper layers inherit earlier flips
-    for name, t_, r_ in (("k", tk, ref["tree_k"]), ("v", tv, ref["tree_v"])):
+    # (two where the reference sits just below a power of two); deeper layers inherit earlier flips,
+    # and are held to twice what the oracle's own nudged evaluation shows in the same measure
+    for name, t_, r_, f_ in (("k", tk, ref["tree_k"], floor_run["tree_k"]), ("v", tv, ref["tree_v"], floor_run["tree_v"])):
         e0 = np.abs(t_[0].cpu().double().numpy() - r_[0])
         bad = int((e0 > 2.0 * bf16_ulp(r_[0]) + 2e-3).sum())      # 2e-3: a flipped bf16 input times a 4-sigma weight
         flips = float((e0 > 0).mean())
         assert bad == 0 and flips < 0.01, (name, bad, flips)
-        e = np.abs(t_.cpu().double().numpy() - r_)
-        assert float((e / (bf16_ulp(r_) + 2e-3)).max()) <= 8.0, name
-    # Noise floor: the oracle against itself with inputs nudged by 3e-6 (the size of fp32-vs-fp64
-    # arithmetic differences).  Rounding flips cascade through the bf16 stages, so two equally
-    # valid bf16 evaluations of one model differ by this much however they are implemented.
-    floor = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16", perturb=3e-6)["logits"]
+        scale = bf16_ulp(r_) + 2e-3
+        e = float((np.abs(t_.cpu().double().numpy() - r_) / scale).max())
+        e_floor = float((np.abs(f_ - r_) / scale).max())
+        print(f"[tree {name}] max error in (ulp + 2e-3) units: gpu {e:.2f}, oracle self-noise {e_floor:.2f}")
+        assert e <= max(8.0, 2.0 * e_floor), (name, e, e_floor)
     floor_max = float(np.abs(floor - ref["logits"]).max())
     pure = oracle.verify_tree(cfg, w, pk, pv, tok, par)["logits"]
     q9999 = float(np.quantile(np.abs(got - ref["logits"]), 0.9999))
