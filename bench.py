@@ -4,6 +4,7 @@
 One step = one pass of the whole path over resident synthetic inputs:
   sx_verify_tree (80-layer Llama-2-70B-shaped bf16 target, 2048 prefix tokens, a seeded best-first
   tree of 2048 tokens) -> sx_accept_walk (t=0.6, top-p 0.9) on the logits it produced ->
+  sx_commit_kv (the accepted nodes' K/V join the prefix cache) ->
   sx_expand_topk (2048 x 32000 draft logits, k=32, best 2048 of 65536).
 Prints one JSON line: verified tree tokens/s, the roofline of the dominant kernel (measured with
 HIP events inside the timed steps) and the CPU oracle timed on a bounded sample of the same work.
@@ -77,7 +78,15 @@ def main():
     torch.cuda.synchronize()
     nparam = sum(v.numel() for lw in w["layers"] for v in lw.values()) + w["embed"].numel() + w["lm_head"].numel()
     log(f"weights: {nparam / 1e9:.2f} G parameters ({nparam * 2 / 1e9:.1f} GB) generated on device in {time.time() - t0:.1f}s")
-    pk, pv = wl.gen_prefix_kv(cfg, P, seed=2, device=dev)
+    pk0, pv0 = wl.gen_prefix_kv(cfg, P, seed=2, device=dev)
+    # the prefix lives in a cache with room for one round's accepted tokens: [L][P + T][Hkv][Dh], rows [0, P) valid
+    pk = torch.zeros((cfg.n_layers, P + T, cfg.n_kv_heads, cfg.head_dim), dtype=pk0.dtype, device=dev)
+    pv = torch.zeros_like(pk)
+    pk[:, :P] = pk0
+    pv[:, :P] = pv0
+    del pk0, pv0
+    tree_k = torch.empty((cfg.n_layers, T, cfg.n_kv_heads, cfg.head_dim), dtype=pk.dtype, device=dev)
+    tree_v = torch.empty_like(tree_k)
     tok, par, _ = wl.gen_best_first_tree(T, k_tree, cfg.vocab, seed=3)
     stats = wl.tree_stats(par)
     tok_d, par_d = torch.from_numpy(tok).to(dev), torch.from_numpy(par).to(dev)
@@ -98,9 +107,10 @@ def main():
     e_n = torch.empty(1, dtype=torch.int32, device=dev)
 
     def step(seed):
-        sx.verify_tree(mw, pk, pv, tok_d, par_d, logits_out=logits, workspace=ws_v)
+        sx.verify_tree(mw, pk, pv, tok_d, par_d, logits_out=logits, tree_k_out=tree_k, tree_v_out=tree_v, workspace=ws_v, P=P)
         sx.accept_walk(logits, tok_d, par_d, temperature, top_p, seed, P, path_out=path_o, tokens_out=toks_o,
                        n_out=n_o, workspace=ws_w)
+        sx.commit_kv(cfg, pk, pv, P, tree_k, tree_v, path_o, n_o)
         sx.expand_topk(dl_d, dc_d, c4["k"], c4["B"], out_row=e_row, out_token=e_tok, out_cum_logp=e_sc, n_out=e_n,
                        workspace=ws_e)
 
@@ -110,7 +120,7 @@ def main():
     assert sx.check_status(ws_v) == 0
     log(f"warmup: {args.warmup} step(s) done")
 
-    launches_per_step = 12 * cfg.n_layers + 16
+    launches_per_step = 12 * cfg.n_layers + 20
     sx.profile_enable(launches_per_step * args.steps + 64)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -172,7 +182,7 @@ def main():
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
                config=dict(workload="%s: %d-layer Llama-2-70B-shaped target (d=%d, %d/%d heads x %d, FFN %d, vocab %d), "
-                           "prefix %d, seeded best-first tree of %d tokens (k=%d), then accept_walk t=%.1f top-p %.1f and "
+                           "prefix %d, seeded best-first tree of %d tokens (k=%d), then accept_walk t=%.1f top-p %.1f, commit_kv and "
                            "expand_topk %dx%d k=%d B=%d" % (args.workload, cfg.n_layers, d, cfg.n_q_heads, cfg.n_kv_heads,
                                                               cfg.head_dim, F, V, P, T, k_tree, temperature, top_p,
                                                               c4["N"], c4["V"], c4["k"], c4["B"]),
@@ -205,7 +215,7 @@ def cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p)
     L2 = min(2, cfg.n_layers)
     wc = dict(embed=cpu(w["embed"]), final_norm=cpu(w["final_norm"]), lm_head=cpu(w["lm_head"]),
               layers=[{k: cpu(v) for k, v in w["layers"][l].items()} for l in range(L2)])
-    pkc, pvc = cpu(pk[:L2]), cpu(pv[:L2])
+    pkc, pvc = cpu(pk[:L2, :P]), cpu(pv[:L2, :P])   # valid rows of the cache
     times = []
     for L in range(1, L2 + 1):
         t0 = time.perf_counter()

@@ -109,6 +109,14 @@ int sx_verify_tree(const sx_weights *w, const void *prefix_k, const void *prefix
                    float *logits_out, void *tree_k_out, void *tree_v_out, void *workspace,
                    size_t workspace_bytes, void *stream);
 
+/* Same as sx_verify_tree with the prefix held in a cache that has room to grow: prefix_k and
+ * prefix_v are device [L][capacity][Hkv][Dh] of which rows [0, P) of every layer are valid
+ * (capacity >= P).  sx_verify_tree is this call with capacity == P. */
+int sx_verify_tree_cached(const sx_weights *w, const void *prefix_k, const void *prefix_v,
+                          int32_t capacity, int32_t P, const int32_t *tree_tokens,
+                          const int32_t *parent_idx, int32_t T, float *logits_out, void *tree_k_out,
+                          void *tree_v_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * sx_accept_walk -- Alg. 1, main loop: p_target := cache[x]; x_next ~ sample(p_target).
  *
@@ -155,6 +163,37 @@ size_t sx_expand_topk_workspace(int32_t N, int32_t V, int32_t k, int32_t B);
 int sx_expand_topk(const float *logits, const float *cum_logp, int32_t N, int32_t V, int32_t k,
                    int32_t B, int32_t *out_row, int32_t *out_token, float *out_cum_logp,
                    int32_t *n_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sx_commit_kv -- Alg. 1, end of the loop body: the tokens the walk accepted join the
+ * context.  Copies the keys and values of the visited nodes into the prefix cache:
+ * cache[l][P + s] = tree[l][path[s]] for every layer l and s < *n.  The node visited at step s
+ * has depth s, so the key it carries was rotated at position P + s, the position it now takes
+ * in the prefix.  The token sampled last (tokens_out[*n - 1] of the walk) is not in the cache:
+ * it is the root of the next round's tree, to be verified at position P + *n.
+ *
+ *   cache_k, cache_v  device [L][capacity][Hkv][Dh], model dtype; rows [0, P) valid before,
+ *                     [0, P + *n) after.  Requires P + T <= capacity (checked on the host).
+ *   tree_k, tree_v    device [L][T][Hkv][Dh], as written by sx_verify_tree
+ *   path, n           device int32 [T] and [1]: path_out and n_out of sx_accept_walk (read on
+ *                     the device: no host round trip between the walk and the commit)
+ * ---------------------------------------------------------------------------------------- */
+int sx_commit_kv(const sx_model_cfg *cfg, void *cache_k, void *cache_v, int32_t capacity, int32_t P,
+                 const void *tree_k, const void *tree_v, int32_t T, const int32_t *path,
+                 const int32_t *n, void *stream);
+
+/* One round of Alg. 1's loop on a stream, without host synchronisation: sx_verify_tree_cached,
+ * sx_accept_walk (uniforms keyed by absolute position, pos0 = P) and sx_commit_kv.  Arguments as
+ * in those calls; tree_k and tree_v are required (device [L][T][Hkv][Dh] scratch or output).
+ * After the stream has run: *n_out accepted nodes were appended to the cache, the new prefix
+ * length is P + *n_out and the next tree is rooted at tokens_out[*n_out - 1].  workspace: at
+ * least sx_specexec_round_workspace(cfg, P, T) bytes, 256-byte aligned. */
+size_t sx_specexec_round_workspace(const sx_model_cfg *cfg, int32_t P, int32_t T);
+int sx_specexec_round(const sx_weights *w, void *cache_k, void *cache_v, int32_t capacity, int32_t P,
+                      const int32_t *tree_tokens, const int32_t *parent_idx, int32_t T,
+                      float temperature, float top_p, uint64_t seed, float *logits, void *tree_k,
+                      void *tree_v, int32_t *path_out, int32_t *tokens_out, int32_t *n_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* Reads the device-side status word of a workspace used by one of the calls above.
  * Synchronises `stream`.  Returns SX_OK, SX_ERR_TREE, or SX_ERR_HIP. */
@@ -215,7 +254,7 @@ int sx_tree_attention_bf16(const void *q, const void *k_tree, const void *v_tree
 typedef enum sx_kernel_class {
   SX_KC_PREP = 1, SX_KC_EMBED, SX_KC_NORM, SX_KC_GEMM_QKV, SX_KC_ROPE, SX_KC_ATTN, SX_KC_GEMM_O,
   SX_KC_GEMM_GATEUP, SX_KC_GEMM_DOWN, SX_KC_GEMM_LMHEAD, SX_KC_ROW_TOPK, SX_KC_SELECT, SX_KC_WALK,
-  SX_KC_F32_PATH
+  SX_KC_F32_PATH, SX_KC_COMMIT
 } sx_kernel_class;
 int sx_profile_enable(int32_t max_records);
 int sx_profile_disable(void);

@@ -8,7 +8,8 @@ import os
 import torch
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
-EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_accept_walk_workspace", "sx_accept_walk",
+EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_commit_kv",
+           "sx_specexec_round_workspace", "sx_specexec_round", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
            "sx_profile_enable", "sx_profile_disable", "sx_profile_read"]
@@ -50,6 +51,15 @@ def _load():
     L.sx_verify_tree.restype = C.c_int
     L.sx_verify_tree.argtypes = [C.POINTER(_Weights), vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.sx_accept_walk_workspace.restype = sz
+    L.sx_verify_tree_cached.restype = C.c_int
+    L.sx_verify_tree_cached.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.sx_commit_kv.restype = C.c_int
+    L.sx_commit_kv.argtypes = [C.POINTER(_Cfg), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp]
+    L.sx_specexec_round_workspace.restype = sz
+    L.sx_specexec_round_workspace.argtypes = [C.POINTER(_Cfg), i32, i32]
+    L.sx_specexec_round.restype = C.c_int
+    L.sx_specexec_round.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, vp, i32, f32, f32, u64, vp, vp, vp, vp, vp,
+                                    vp, vp, sz, vp]
     L.sx_accept_walk_workspace.argtypes = [i32, i32]
     L.sx_accept_walk.restype = C.c_int
     L.sx_accept_walk.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
@@ -86,7 +96,7 @@ lib = _load()
 
 KERNEL_CLASSES = {1: "prep", 2: "embed", 3: "rmsnorm", 4: "gemm_qkv", 5: "rope", 6: "tree_attn", 7: "gemm_o",
                   8: "gemm_gateup_swiglu", 9: "gemm_down", 10: "gemm_lmhead", 11: "row_topk", 12: "global_select",
-                  13: "accept_walk", 14: "f32_path"}
+                  13: "accept_walk", 14: "f32_path", 15: "commit_kv"}
 
 
 def status_string(code: int) -> str:
@@ -145,20 +155,60 @@ def verify_tree_workspace(cfg, P: int, T: int) -> int:
 
 
 def verify_tree(weights: ModelWeights, prefix_k, prefix_v, tree_tokens, parent_idx, logits_out=None,
-                tree_k_out=None, tree_v_out=None, workspace=None, stream=None):
+                tree_k_out=None, tree_v_out=None, workspace=None, stream=None, P=None):
     """sx_verify_tree.  Returns (logits_out, workspace); allocates them with torch when not given."""
     cfg = weights.cfg
     T = int(tree_tokens.numel())
-    P = 0 if prefix_k is None else int(prefix_k.shape[1])
+    capacity = 0 if prefix_k is None else int(prefix_k.shape[1])
+    P = capacity if P is None else int(P)          # P < capacity: the prefix is a cache with room to grow
     if logits_out is None:
         logits_out = torch.empty((T, cfg.vocab), dtype=torch.float32, device=weights.device)
     if workspace is None:
         workspace = _workspace(verify_tree_workspace(cfg, P, T), weights.device)
-    rc = lib.sx_verify_tree(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), P, _ptr(tree_tokens), _ptr(parent_idx), T,
-                            _ptr(logits_out), _ptr(tree_k_out), _ptr(tree_v_out), _ptr(workspace), workspace.numel(),
-                            _stream(stream))
+    rc = lib.sx_verify_tree_cached(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), capacity, P, _ptr(tree_tokens),
+                                   _ptr(parent_idx), T, _ptr(logits_out), _ptr(tree_k_out), _ptr(tree_v_out),
+                                   _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "sx_verify_tree")
     return logits_out, workspace
+
+
+def commit_kv(cfg, cache_k, cache_v, P: int, tree_k, tree_v, path, n, stream=None):
+    """sx_commit_kv: cache[l][P + s] = tree[l][path[s]] for s < n (n a device int32 tensor)."""
+    c = _make_cfg(cfg)
+    capacity, T = int(cache_k.shape[1]), int(tree_k.shape[1])
+    _check(lib.sx_commit_kv(C.byref(c), _ptr(cache_k), _ptr(cache_v), capacity, P, _ptr(tree_k), _ptr(tree_v), T, _ptr(path),
+                            _ptr(n), _stream(stream)), "sx_commit_kv")
+
+
+class RoundBuffers:
+    """Device buffers of sx_specexec_round for trees of up to T nodes (allocated once, reused every round)."""
+
+    def __init__(self, weights: ModelWeights, capacity: int, T: int):
+        cfg, dev = weights.cfg, weights.device
+        dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.T = T
+        self.logits = torch.empty((T, cfg.vocab), dtype=torch.float32, device=dev)
+        self.tree_k = torch.empty((cfg.n_layers, T, cfg.n_kv_heads, cfg.head_dim), dtype=dt, device=dev)
+        self.tree_v = torch.empty_like(self.tree_k)
+        self.path = torch.empty(T, dtype=torch.int32, device=dev)
+        self.tokens = torch.empty(T, dtype=torch.int32, device=dev)
+        self.n = torch.zeros(1, dtype=torch.int32, device=dev)
+        c = _make_cfg(cfg)
+        self.workspace = _workspace(lib.sx_specexec_round_workspace(C.byref(c), capacity, T), dev)
+
+
+def specexec_round(weights: ModelWeights, cache_k, cache_v, P: int, tree_tokens, parent_idx, temperature: float,
+                   top_p: float, seed: int, buf: RoundBuffers, stream=None):
+    """sx_specexec_round: verify the tree against cache rows [0, P), walk it, append the accepted nodes' K/V to
+    the cache.  Results are in buf (path, tokens, n, logits); nothing is synchronised."""
+    T = int(tree_tokens.numel())
+    capacity = int(cache_k.shape[1])
+    rc = lib.sx_specexec_round(C.byref(weights.c), _ptr(cache_k), _ptr(cache_v), capacity, P, _ptr(tree_tokens),
+                               _ptr(parent_idx), T, temperature, top_p, seed, _ptr(buf.logits), _ptr(buf.tree_k),
+                               _ptr(buf.tree_v), _ptr(buf.path), _ptr(buf.tokens), _ptr(buf.n), _ptr(buf.workspace),
+                               buf.workspace.numel(), _stream(stream))
+    _check(rc, "sx_specexec_round")
+    return buf
 
 
 def accept_walk(logits, tree_tokens, parent_idx, temperature: float, top_p: float, seed: int, pos0: int,

@@ -59,7 +59,7 @@ static inline int sx_attn_nodes_per_tile(int Hq, int Hkv) { return 128 / (Hq / H
 // ---- optional event timing around single launches (prof.hip) -----------------------------------------
 enum {
   SX_K_PREP = 1, SX_K_EMBED, SX_K_NORM, SX_K_GEMM_QKV, SX_K_ROPE, SX_K_ATTN, SX_K_GEMM_O, SX_K_GEMM_GATEUP,
-  SX_K_GEMM_DOWN, SX_K_GEMM_LMHEAD, SX_K_ROW_TOPK, SX_K_SELECT, SX_K_WALK, SX_K_F32_PATH
+  SX_K_GEMM_DOWN, SX_K_GEMM_LMHEAD, SX_K_ROW_TOPK, SX_K_SELECT, SX_K_WALK, SX_K_F32_PATH, SX_K_COMMIT
 };
 void sx_prof_begin(int tag, hipStream_t st);
 void sx_prof_end(hipStream_t st);

@@ -113,6 +113,15 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
                               const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T, float* logits_out,
                               void* tree_k_out, void* tree_v_out, void* workspace, size_t workspace_bytes,
                               void* stream) {
+  return sx_verify_tree_cached(w, prefix_k, prefix_v, P, P, tree_tokens, parent_idx, T, logits_out, tree_k_out,
+                               tree_v_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int sx_verify_tree_cached(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t capacity,
+                                     int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T,
+                                     float* logits_out, void* tree_k_out, void* tree_v_out, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  if (capacity < P) return SX_ERR_SHAPE;
   if (!w || !tree_tokens || !parent_idx || !logits_out || !w->embed || !w->layers || !w->final_norm || !w->lm_head)
     return SX_ERR_NULL;
   const sx_model_cfg& c = w->cfg;
@@ -145,7 +154,7 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
-    const size_t kv_layer = (size_t)l * T * Nkv * es, pre_layer = (size_t)l * P * Nkv * es;
+    const size_t kv_layer = (size_t)l * T * Nkv * es, pre_layer = (size_t)l * capacity * Nkv * es;
     void* tk = tree_k_out ? static_cast<char*>(tree_k_out) + kv_layer : L.tk;
     void* tv = tree_v_out ? static_cast<char*>(tree_v_out) + kv_layer : L.tv;
     const void* pk = P > 0 ? static_cast<const char*>(prefix_k) + pre_layer : nullptr;
@@ -197,6 +206,73 @@ extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const v
   else
     SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, T, V, d, V, false, st));
   return SX_OK;
+}
+
+// ---- KV commit and one whole round (Alg. 1, loop body) ----------------------------------------------
+namespace {
+// cache[l][P + s][:] = tree[l][path[s]][:] for s < *n; one workgroup per (layer, s mod gridDim.y), 16 bytes per lane
+__global__ __launch_bounds__(256) void commit_kv_kernel(char* __restrict__ cache_k, char* __restrict__ cache_v,
+                                                        const char* __restrict__ tree_k, const char* __restrict__ tree_v,
+                                                        const int* __restrict__ path, const int* __restrict__ n_dev,
+                                                        int capacity, int P, int T, int row_bytes) {
+  const int l = blockIdx.x;
+  int n = *n_dev;
+  n = n < 0 ? 0 : (n > T ? T : n);
+  if (P + n > capacity) n = capacity - P;  // the host checked P + T <= capacity; never write past the cache
+  for (int s = blockIdx.y; s < n; s += gridDim.y) {
+    int node = path[s];
+    node = node < 0 ? 0 : (node >= T ? T - 1 : node);
+    const size_t src = ((size_t)l * T + node) * row_bytes, dst = ((size_t)l * capacity + P + s) * row_bytes;
+    for (int b = threadIdx.x * 16; b < row_bytes; b += 256 * 16) {
+      *reinterpret_cast<u32x4*>(cache_k + dst + b) = *reinterpret_cast<const u32x4*>(tree_k + src + b);
+      *reinterpret_cast<u32x4*>(cache_v + dst + b) = *reinterpret_cast<const u32x4*>(tree_v + src + b);
+    }
+  }
+}
+}  // namespace
+
+extern "C" int sx_commit_kv(const sx_model_cfg* cfg, void* cache_k, void* cache_v, int32_t capacity, int32_t P,
+                            const void* tree_k, const void* tree_v, int32_t T, const int32_t* path, const int32_t* n,
+                            void* stream) {
+  if (!cfg || !cache_k || !cache_v || !tree_k || !tree_v || !path || !n) return SX_ERR_NULL;
+  if (cfg->dtype != SX_F32 && cfg->dtype != SX_BF16) return SX_ERR_DTYPE;
+  const size_t es = cfg->dtype == SX_BF16 ? 2 : 4;
+  const size_t row_bytes = (size_t)cfg->n_kv_heads * cfg->head_dim * es;
+  if (cfg->n_layers < 1 || T < 1 || P < 0 || (long long)P + T > capacity || row_bytes == 0 || row_bytes % 16 != 0)
+    return SX_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  sx_prof_begin(SX_K_COMMIT, st);
+  commit_kv_kernel<<<dim3(cfg->n_layers, 8), 256, 0, st>>>(static_cast<char*>(cache_k), static_cast<char*>(cache_v),
+                                                           static_cast<const char*>(tree_k), static_cast<const char*>(tree_v),
+                                                           path, n, capacity, P, T, (int)row_bytes);
+  sx_prof_end(st);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+extern "C" size_t sx_specexec_round_workspace(const sx_model_cfg* cfg, int32_t P, int32_t T) {
+  const size_t v = sx_verify_tree_workspace(cfg, P, T);
+  if (v == 0) return 0;
+  const size_t a = sx_accept_walk_workspace(T, cfg->vocab);
+  return ((v + 255) & ~(size_t)255) + a;
+}
+
+extern "C" int sx_specexec_round(const sx_weights* w, void* cache_k, void* cache_v, int32_t capacity, int32_t P,
+                                 const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T, float temperature,
+                                 float top_p, uint64_t seed, float* logits, void* tree_k, void* tree_v,
+                                 int32_t* path_out, int32_t* tokens_out, int32_t* n_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!w || !logits || !tree_k || !tree_v || !path_out || !tokens_out || !n_out || !workspace) return SX_ERR_NULL;
+  if ((long long)P + T > capacity) return SX_ERR_SHAPE;
+  const size_t v = sx_verify_tree_workspace(&w->cfg, P, T);
+  if (v == 0) return SX_ERR_SHAPE;
+  const size_t v_al = (v + 255) & ~(size_t)255;
+  if (workspace_bytes < v_al + sx_accept_walk_workspace(T, w->cfg.vocab)) return SX_ERR_WORKSPACE;
+  SX_TRY(sx_verify_tree_cached(w, cache_k, cache_v, capacity, P, tree_tokens, parent_idx, T, logits, tree_k, tree_v,
+                               workspace, v, stream));
+  SX_TRY(sx_accept_walk(logits, nullptr, tree_tokens, parent_idx, T, w->cfg.vocab, temperature, top_p, seed, P, path_out,
+                        tokens_out, n_out, static_cast<char*>(workspace) + v_al, workspace_bytes - v_al, stream));
+  return sx_commit_kv(&w->cfg, cache_k, cache_v, capacity, P, tree_k, tree_v, T, path_out, n_out, stream);
 }
 
 // Attention alone: lays out only what it needs at the head of the workspace.

@@ -151,6 +151,93 @@ def test_c1_walk_on_gpu_logits_equals_sequential_sampling(sx, c1):
     assert checked >= 4
 
 
+def test_c1_rounds_with_kv_commit_equal_sequential_sampling(sx, c1):
+    """Alg. 1's outer loop on the GPU: verify, walk, commit the accepted nodes' K/V to the cache, root the
+    next tree at the last sampled token -- three rounds per seed through sx_specexec_round.  The emitted
+    stream must be the oracle's token-by-token sample (Sect. 4.1), and the cache rows the rounds appended
+    must be the keys/values an ordinary causal forward over those tokens produces."""
+    cfg, w, wn, pk, pv = c1
+    P0 = pk.shape[1]
+    w8 = dict(w, lm_head=w["lm_head"] * 20.0)
+    wn8 = dict(wn, lm_head=wn["lm_head"] * 20.0)
+    mw = sx.ModelWeights(cfg, weights_to(w8, dev()))
+    rounds, T = 3, 16
+    capacity = P0 + rounds * T
+    r = np.random.default_rng(11)
+    checked = 0
+    for s in range(10):
+        first = int(r.integers(0, cfg.vocab))
+        truth = oracle.sequential_sample(cfg, wn8, pk, pv, first, 3 * rounds + 3, 0.6, 0.9, seed=s, pos0=P0)
+        # margin check along the true stream: every decision must be safely away from a tie
+        seq, safe = [first], True
+        for x in truth:
+            lg = oracle.path_forward(cfg, wn8, pk, pv, seq)
+            tok_, m = oracle.sample_token(lg, 0.6, 0.9, oracle.uniform01(s, P0 + len(seq)))
+            assert tok_ == x
+            safe &= min(m["m_p"], m["m_u"]) > 1e-3
+            seq.append(x)
+        if not safe:
+            continue
+        cache_k = torch.zeros((cfg.n_layers, capacity, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device=dev())
+        cache_v = torch.zeros_like(cache_k)
+        cache_k[:, :P0] = to_dev(torch.as_tensor(pk), torch.float32)
+        cache_v[:, :P0] = to_dev(torch.as_tensor(pv), torch.float32)
+        buf = sx.RoundBuffers(mw, capacity, T)
+        P, root, emitted = P0, first, []
+        for rd in range(rounds):
+            done = len(emitted)
+            # the root, a chain of the next two true tokens, and distractor children that do not carry them
+            tok, par = [root], [-1]
+            spine = 0
+            for x in truth[done:done + 2]:
+                for _ in range(3):
+                    d = int(r.integers(0, cfg.vocab))
+                    if d != x:
+                        tok.append(d)
+                        par.append(spine)
+                tok.append(x)
+                par.append(spine)
+                spine = len(tok) - 1
+            tok, par = np.array(tok, np.int32), np.array(par, np.int32)
+            sx.specexec_round(mw, cache_k, cache_v, P, to_dev(tok), to_dev(par), 0.6, 0.9, s, buf)
+            torch.cuda.synchronize()
+            assert sx.check_status(buf.workspace) == 0
+            n = int(buf.n.item())
+            assert n == 3                                            # both draft tokens accepted, then one more
+            toks = buf.tokens[:n].cpu().tolist()
+            emitted += toks
+            P += n
+            root = toks[-1]
+        assert emitted == truth[:len(emitted)]
+        # the context is first + emitted[:-1]; its K/V at positions P0.. are what the rounds appended
+        _, ks, vs = oracle.path_forward(cfg, wn8, pk, pv, [first] + emitted[:-1], return_kv=True)
+        assert P == P0 + len(emitted)
+        np.testing.assert_allclose(cache_k[:, P0:P].cpu().double().numpy(), ks, atol=1e-4)
+        np.testing.assert_allclose(cache_v[:, P0:P].cpu().double().numpy(), vs, atol=1e-4)
+        assert float(cache_k[:, P:].abs().max()) == 0.0             # nothing written past the accepted rows
+        checked += 1
+    assert checked >= 4
+
+
+def test_commit_kv_bf16_gathers_path_rows(sx):
+    """sx_commit_kv alone, bf16 rows of 2 KB, n read from the device: byte-exact gather, rows past n untouched."""
+    cfg = wl.ModelCfg(3, 1024, 8, 8, 128, 2752, 4000, dtype="bf16")
+    T, P, cap = 40, 10, 64
+    tk = wl.hash_normal(5, (3, T, 8, 128), dtype=torch.bfloat16).to(dev())
+    tv = wl.hash_normal(6, (3, T, 8, 128), dtype=torch.bfloat16).to(dev())
+    ck = torch.full((3, cap, 8, 128), 7.0, dtype=torch.bfloat16, device=dev())
+    cv = torch.full((3, cap, 8, 128), 9.0, dtype=torch.bfloat16, device=dev())
+    path = torch.tensor([0, 3, 17, 39, 5, 6] + [0] * (T - 6), dtype=torch.int32, device=dev())
+    n = torch.tensor([4], dtype=torch.int32, device=dev())
+    sx.commit_kv(cfg, ck, cv, P, tk, tv, path, n)
+    torch.cuda.synchronize()
+    for s_, node in enumerate([0, 3, 17, 39]):
+        assert torch.equal(ck[:, P + s_], tk[:, node]) and torch.equal(cv[:, P + s_], tv[:, node])
+    assert bool((ck[:, :P] == 7.0).all()) and bool((ck[:, P + 4:] == 7.0).all()) and bool((cv[:, P + 4:] == 9.0).all())
+    with pytest.raises(sx.SxError):                                   # P + T must fit the cache
+        sx.commit_kv(cfg, ck, cv, 30, tk, tv, path, n)
+
+
 # ------------------------------------------------------------------------------------------------
 # bf16 building blocks
 # ------------------------------------------------------------------------------------------------

@@ -136,3 +136,42 @@ def test_duplicate_sibling_goes_to_lowest_index():
     logits[3, 2] = 0.0
     res = oracle.accept_walk(logits, tok, par, 0.0, 1.0, seed=1, pos0=0)
     assert res["path"] == [0, 1, 3] and res["tokens"] == [3, 9, 2]
+
+
+def test_generation_over_many_rounds_equals_sequential_sampling(model):
+    """Sect. 4.1 across rounds (Alg. 1's outer loop): whatever trees are offered each round -- here random
+    ones over a 12-token vocabulary, so rounds accept 0 to several draft tokens -- the emitted stream is the
+    token-by-token sample with the same seed, and the context grows by exactly the emitted tokens."""
+    cfg, w, _, _ = model
+    prompt = [int(t) for t in gen_tokens(5, cfg.vocab, seed=31)]
+    for s in range(6):
+        def tree_fn(context, r, s=s):
+            tok, par = gen_uniform_tree(30, cfg.vocab, seed=1000 * s + r)
+            tok = tok.copy()
+            tok[0] = context[-1]
+            return tok, par
+        out, per_round = oracle.specexec_generate(cfg, w, prompt, 5, tree_fn, 0.6, 0.9, seed=s)
+        assert len(per_round) == 5 and min(per_round) >= 1 and sum(per_round) == len(out)
+        _, pk, pv = oracle.path_forward(cfg, w, None, None, prompt[:-1], return_kv=True)
+        ref = oracle.sequential_sample(cfg, w, pk, pv, prompt[-1], len(out), 0.6, 0.9, seed=s, pos0=len(prompt) - 1)
+        assert out == ref
+    # trees that contain the next two tokens of the true stream (plus random siblings): such rounds must
+    # accept exactly those two and emit a third
+    _, pk, pv = oracle.path_forward(cfg, w, None, None, prompt[:-1], return_kv=True)
+    truth = oracle.sequential_sample(cfg, w, pk, pv, prompt[-1], 12, 0.6, 0.9, seed=3, pos0=len(prompt) - 1)
+
+    def informed(context, r):
+        done = len(context) - len(prompt)
+        tok, par = gen_uniform_tree(12, cfg.vocab, seed=77 + r)
+        tok, par = list(tok), list(par)
+        tok[0] = context[-1]
+        tok += [truth[done], truth[done + 1]]
+        par += [0, len(tok) - 2]
+        # random siblings that happen to carry the true token would be walked first: rename them
+        for i in range(1, len(tok) - 2):
+            if par[i] == 0 and tok[i] == truth[done]:
+                tok[i] = (tok[i] + 1) % cfg.vocab
+        return np.array(tok, np.int32), np.array(par, np.int32)
+
+    out, per_round = oracle.specexec_generate(cfg, w, prompt, 3, informed, 0.6, 0.9, seed=3)
+    assert out == truth[:len(out)] and all(n >= 3 for n in per_round)
