@@ -10,6 +10,10 @@
 // (value descending, index ascending).  Rows where the bound is useless (massive ties) fall back
 // to an exact bitwise threshold search over the same registers.
 //
+// Vocabularies above 32768 do not fit the registers of such a workgroup; row_topk_stream_kernel
+// streams the row instead (running maximum and rescaled sum per lane) and takes the candidates
+// from a second sweep that L2 serves.
+//
 // Kernel 2, global_select_kernel: one workgroup picks the B best of the N*k candidates by
 // score = cum_logp[row] + logp, ties to the lower flat index, and writes them in that order.
 #include "kernels.h"
@@ -162,11 +166,16 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
   for (int j = 0; j < IPT4; ++j) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const int idx = (j * THREADS + tid) * 4 + c;
-      if (idx < V && v[4 * j + c] >= t0) {
-        const int pos = atomicAdd(&s_cnt, 1);
-        if (pos < kCandCap)
-          cand[pos] = ((unsigned long long)(~f32_order_key(v[4 * j + c])) << 32) | (unsigned)idx;
+      // hits are rare (a few dozen per row): one compare and one scalar branch per register, and the
+      // divergent code only where some lane of the wave has one
+      const bool hit = v[4 * j + c] >= t0;
+      if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+        const int idx = (j * THREADS + tid) * 4 + c;
+        if (hit && idx < V) {
+          const int pos = atomicAdd(&s_cnt, 1);
+          if (pos < kCandCap)
+            cand[pos] = ((unsigned long long)(~f32_order_key(v[4 * j + c])) << 32) | (unsigned)idx;
+        }
       }
     }
   }
@@ -177,20 +186,201 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
   if (small_k && C <= 64) {
     // ---- the usual case: a few dozen candidates, ordered by one wave in registers -------------------
     if (tid >= 64) return;
-    unsigned long long x64 = tid < C ? cand[tid] : ~0ull;
+    // keys are distinct (the index is part of them), so a candidate's place is the number of smaller
+    // keys: 64 scalar broadcasts and compares, no sorting network and no cross-lane latency chain
+    const unsigned long long x64 = tid < C ? cand[tid] : ~0ull;
+    const unsigned xlo = (unsigned)x64, xhi = (unsigned)(x64 >> 32);
+    int place = 0;
 #pragma unroll
-    for (int size = 2; size <= 64; size <<= 1)
-#pragma unroll
-      for (int stride = size >> 1; stride > 0; stride >>= 1) {
-        const unsigned long long other = __shfl_xor(x64, stride, 64);
-        const bool keep_min = ((tid & stride) == 0) == ((tid & size) == 0);
-        x64 = keep_min ? (x64 < other ? x64 : other) : (x64 < other ? other : x64);
-      }
-    if (tid < k) {
-      const float val = f32_from_order_key(~(unsigned)(x64 >> 32));
+    for (int j = 0; j < 64; ++j) {
+      const unsigned olo = __builtin_amdgcn_readlane(xlo, j), ohi = __builtin_amdgcn_readlane(xhi, j);
+      place += (ohi < xhi || (ohi == xhi && olo < xlo)) ? 1 : 0;
+    }
+    if (tid < C && place < k) {
+      const float val = f32_from_order_key(~xhi);
       const float lp = val - lse;
-      const size_t o = row * (size_t)k + tid;
-      topk_idx[o] = (int)(unsigned)(x64 & 0xFFFFFFFFull);
+      const size_t o = row * (size_t)k + place;
+      topk_idx[o] = (int)xlo;
+      topk_logp[o] = lp;
+      if (score) score[o] = cl + lp;
+    }
+    return;
+  }
+  __syncthreads();
+  if (C > kCandCap) {  // the bound was useless (massive ties): exact search, re-reading the row from L2
+    C = exact_topk_from_memory<THREADS>(x, V, k, redi, &s_cnt, cand);
+  }
+
+  // ---- general case: order the candidates in LDS and emit the first k --------------------------------
+  const int n = next_pow2(C < 2 ? 2 : C);
+  for (int i = C + tid; i < n; i += THREADS) cand[i] = ~0ull;
+  block_bitonic_sort_u64<THREADS>(cand, n);
+  for (int c = tid; c < k; c += THREADS) {
+    const unsigned long long e = cand[c];
+    const float val = f32_from_order_key(~(unsigned)(e >> 32));
+    const float lp = val - lse;
+    const size_t o = row * (size_t)k + c;
+    topk_idx[o] = (int)(unsigned)(e & 0xFFFFFFFFull);
+    topk_logp[o] = lp;
+    if (score) score[o] = cl + lp;
+  }
+}
+
+// Lane `tid` owns the float4 slots tid, tid + THREADS, ... of the row (element index 4 * slot + c).
+// Pass 1 streams the row from HBM four slots at a time, keeping only a running maximum and a sum of
+// exponentials relative to it; pass 2 streams it again, now from L2, and keeps the few entries >= t0.
+// Few registers whatever V is: used for vocabularies too large for the register-resident kernel above.
+template <int THREADS, bool VEC>
+__global__ __launch_bounds__(THREADS) void row_topk_stream_kernel(const float* __restrict__ logits,
+                                                           const float* __restrict__ cum_logp, int V, int k,
+                                                           float* __restrict__ topk_logp,
+                                                           int* __restrict__ topk_idx,
+                                                           float* __restrict__ score) {
+  constexpr int NW = THREADS / 64;
+  constexpr int U = 4;  // float4 slots in flight per lane
+  __shared__ float smax[THREADS];
+  __shared__ float redf[32];
+  __shared__ float s_gmax[64];
+  __shared__ int redi[16];
+  __shared__ float s_t0;
+  __shared__ int s_cnt;
+  __shared__ unsigned long long cand[kCandCap];
+
+  const int tid = threadIdx.x;
+  const size_t row = blockIdx.x;
+  const float* x = logits + row * (size_t)V;
+  const float NEG_INF = -__builtin_huge_valf();
+  const int nslot = (V + 3) / 4;
+
+  // slots [s0, s0 + U * THREADS) of the row into c[U * 4]; out-of-range elements read as -inf
+  auto load_chunk = [&](int s0, float (&c)[U * 4]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int slot = s0 + u * THREADS + tid;
+      if (VEC) {
+        if (slot < nslot) {
+          const float4 t = *reinterpret_cast<const float4*>(x + 4 * (size_t)slot);
+          c[4 * u + 0] = t.x; c[4 * u + 1] = t.y; c[4 * u + 2] = t.z; c[4 * u + 3] = t.w;
+        } else {
+          c[4 * u + 0] = c[4 * u + 1] = c[4 * u + 2] = c[4 * u + 3] = NEG_INF;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[4 * u + e] = (4 * slot + e < V) ? x[4 * (size_t)slot + e] : NEG_INF;
+      }
+    }
+  };
+
+  // ---- pass 1: lane maximum tm and lane sum se of exp(x - tm), rescaled whenever tm rises ----------------
+  float tm = NEG_INF, se = 0.f;
+  for (int s0 = 0; s0 < nslot; s0 += U * THREADS) {
+    float c[U * 4];
+    load_chunk(s0, c);
+    float cm = c[0];
+#pragma unroll
+    for (int e = 1; e < U * 4; ++e) cm = fmaxf(cm, c[e]);
+    if (cm > tm) {  // also the first finite chunk: exp2(-inf) = 0 clears the (empty) sum
+      se *= __builtin_amdgcn_exp2f((tm - cm) * kLog2e);
+      tm = cm;
+    }
+    if (tm > NEG_INF) {
+#pragma unroll
+      for (int e = 0; e < U * 4; ++e) se += __builtin_amdgcn_exp2f((c[e] - tm) * kLog2e);
+    }
+  }
+
+  // ---- maxima: per group of GS lanes (64 groups), per wave ---------------------------------------------
+  constexpr int GS = THREADS / 64;
+  float gm = tm;
+#pragma unroll
+  for (int o = 1; o < GS; o <<= 1) gm = fmaxf(gm, __shfl_xor(gm, o, 64));
+  const float wmx = wave_max(gm);
+  const bool small_k = k <= 64;  // uniform
+  if ((tid & 63) == 0) redf[tid >> 6] = wmx;
+  if ((tid & (GS - 1)) == 0) s_gmax[tid / GS] = gm;
+  if (!small_k) smax[tid] = tm;
+  if (tid == 0) s_cnt = 0;
+  __syncthreads();  // (1)
+  float M = redf[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) M = fmaxf(M, redf[w]);
+
+  // ---- lane sums brought to the row maximum; meanwhile wave 0 ranks the group maxima -----------------------
+  // t0 = k-th largest of a set of group maxima (rank by value, then group id) is a lower bound of
+  // the k-th largest entry.  k <= 64: 64 groups ranked by one wave with lane broadcasts (hardly
+  // looser than per-lane maxima and far cheaper); else every lane is a group.
+  se = tm > NEG_INF ? se * __builtin_amdgcn_exp2f((tm - M) * kLog2e) : 0.f;
+  se = wave_sum(se);
+  if ((tid & 63) == 0) redf[NW + (tid >> 6)] = se;
+  if (small_k) {
+    if (tid < 64) {
+      const float g = s_gmax[tid];
+      int rank = 0;
+#pragma unroll
+      for (int j = 0; j < 64; ++j) {
+        const float o = __shfl(g, j, 64);
+        rank += (o > g || (o == g && j < tid)) ? 1 : 0;
+      }
+      if (rank == k - 1) s_t0 = g;
+    }
+  } else {
+    int rank = 0;
+    for (int j = 0; j < THREADS; ++j) {
+      const float o = smax[j];
+      rank += (o > tm || (o == tm && j < tid)) ? 1 : 0;
+    }
+    if (rank == k - 1) s_t0 = tm;
+  }
+  __syncthreads();  // (2)
+  float S = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) S += redf[NW + w];
+  const float lse = M + logf(S);
+  const float t0 = s_t0;
+
+  // ---- pass 2: gather candidates >= t0 (the row comes from L2 this time) -------------------------------
+  // Hits are rare (a few dozen per row): one compare and one scalar branch per value, and the divergent
+  // code only where some lane of the wave has one.  A lane whose maximum is below t0 holds none, and a
+  // wave of such lanes skips its share of the row altogether.
+  if (__builtin_amdgcn_ballot_w64(tm >= t0) != 0ull) {
+    for (int s0 = 0; s0 < nslot; s0 += U * THREADS) {
+      float c[U * 4];
+      load_chunk(s0, c);
+#pragma unroll
+      for (int e = 0; e < U * 4; ++e) {
+        const bool hit = c[e] >= t0;
+        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+          const int idx = 4 * (s0 + (e >> 2) * THREADS + tid) + (e & 3);
+          if (hit && idx < V) {
+            const int pos = atomicAdd(&s_cnt, 1);
+            if (pos < kCandCap) cand[pos] = ((unsigned long long)(~f32_order_key(c[e])) << 32) | (unsigned)idx;
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();  // (3)
+  int C = s_cnt;
+  const float cl = cum_logp ? cum_logp[row] : 0.f;
+
+  if (small_k && C <= 64) {
+    // ---- the usual case: a few dozen candidates, placed by one wave in registers --------------------
+    // keys are distinct (the index is part of them), so a candidate's place is the number of smaller
+    // keys: 64 scalar broadcasts and compares, no sorting network and no cross-lane latency chain
+    if (tid >= 64) return;
+    const unsigned long long x64 = tid < C ? cand[tid] : ~0ull;
+    const unsigned xlo = (unsigned)x64, xhi = (unsigned)(x64 >> 32);
+    int place = 0;
+#pragma unroll
+    for (int j = 0; j < 64; ++j) {
+      const unsigned olo = __builtin_amdgcn_readlane(xlo, j), ohi = __builtin_amdgcn_readlane(xhi, j);
+      place += (ohi < xhi || (ohi == xhi && olo < xlo)) ? 1 : 0;
+    }
+    if (tid < C && place < k) {
+      const float val = f32_from_order_key(~xhi);
+      const float lp = val - lse;
+      const size_t o = row * (size_t)k + place;
+      topk_idx[o] = (int)xlo;
       topk_logp[o] = lp;
       if (score) score[o] = cl + lp;
     }
@@ -355,8 +545,11 @@ int row_topk_dispatch(const float* logits, const float* cum, int N, int V, int k
   else if (V <= 4096) launch_row<256, 4>(logits, cum, N, V, k, lp, idx, score, st);
   else if (V <= 16384) launch_row<256, 16>(logits, cum, N, V, k, lp, idx, score, st);
   else if (V <= 32768) launch_row<512, 16>(logits, cum, N, V, k, lp, idx, score, st);
-  else if (V <= 65536) launch_row<1024, 16>(logits, cum, N, V, k, lp, idx, score, st);
-  else launch_row<1024, 32>(logits, cum, N, V, k, lp, idx, score, st);
+  else {  // the row no longer fits the registers of a workgroup that leaves room for a second one
+    const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(logits) & 15) == 0);
+    if (vec) row_topk_stream_kernel<512, true><<<N, 512, 0, st>>>(logits, cum, V, k, lp, idx, score);
+    else row_topk_stream_kernel<512, false><<<N, 512, 0, st>>>(logits, cum, V, k, lp, idx, score);
+  }
   SX_LAUNCH_CHECK();
   return SX_OK;
 }
