@@ -10,13 +10,22 @@
 // node's own ancestors.  Work on the tree part is therefore proportional to what is attended.
 //
 // Data flow per key tile (flash-style online softmax):
-//   K rows  -> LDS [key][d], 16-byte chunks XOR-swizzled by key & 15 (16 lanes x 16 B per LDS cycle);
-//   V rows  -> LDS transposed [d][key slot], packed on the fly from 4-byte column pairs;
+//   K and V rows -> LDS by buffer loads that write LDS directly (no staging registers, no LDS-write
+//         instructions, nothing to transpose by hand: staging through registers and packing V^T
+//         with bit operations was 46% of the kernel's time).  Both tiles are [key][128 d] rows of
+//         256 bytes, two stages each, one barrier per tile.  16-byte chunks are XOR-swizzled, K by
+//         key & 15 and V by (key & 3) << 2, each conflict-free for the way it is read; the
+//         swizzle is applied on the global side (a wave's 1 KB of LDS per instruction is contiguous).
 //   S^T = K Q^T   (MFMA 32x32x16: A = K from LDS, B = Q held in registers for the whole kernel).
 //         Computing the transpose puts a query row in ONE lane pair (l, l^32): max and sum need a
 //         single cross-lane exchange, and the probabilities already sit in the B-operand layout.
-//   O^T += V^T P^T (A = V^T from LDS, B = P).  P is split into a bf16 head and a bf16 remainder
-//         (two MFMAs) so that the probabilities carry ~16 mantissa bits instead of 8; running
+//   O^T += V^T P^T (A = V^T, B = P).  V^T fragments come out of the row-major V tile through the
+//         LDS transpose read (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i % 4 of
+//         the 8 bytes addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4): lane s of a
+//         group points at V[key0 + s / 4][d0 + 4 (s % 4) ..], lane i receives V[key0 .. key0 + 3][d0 + i].
+//         P is split into a bf16 head and a bf16 remainder (two MFMAs) so that the probabilities
+//         carry ~16 mantissa bits instead of 8: an error of 1e-4 relative before the output's bf16
+//         rounding flips ~7% of those roundings against a correctly rounded reference.  Running
 //         max / sum / rescale factors of a row live in the same lane as its accumulators.
 #include "kernels.h"
 
@@ -26,6 +35,7 @@ constexpr int DH = 128;
 constexpr int QROWS = 128;
 constexpr int KTILE = 64;
 constexpr int kThreads = 256;
+constexpr int kTileBytes = KTILE * DH * 2;  // 16 KB: one K or V tile
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnArgs {
@@ -41,8 +51,14 @@ struct AttnArgs {
   int T, P, Hq, Hkv, G, npt, W64;
 };
 
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, -1, 0x00020000);
+}
 __device__ __forceinline__ int ks_off(int key, int chunk) { return key * (DH * 2) + ((chunk ^ (key & 15)) << 4); }
-__device__ __forceinline__ int vt_off(int d, int chunk) { return d * (KTILE * 2) + ((chunk ^ ((d ^ (d >> 3)) & 7)) << 4); }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_cvt_pk_bf16_f32
@@ -50,11 +66,26 @@ __device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_
   return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
+// s_waitcnt: all vector-memory operations (the copies) and all LDS reads of this wave done
+constexpr int kWaitAll = 0x0070;
+// The barrier intrinsic does not order memory operations for the compiler, and a workgroup fence would be
+// heavier than needed; empty asm statements that claim to touch memory pin LDS reads and copies to their side.
+#define SX_WAIT_BARRIER()                  \
+  asm volatile("" ::: "memory");           \
+  __builtin_amdgcn_s_waitcnt(kWaitAll);    \
+  __builtin_amdgcn_s_barrier();            \
+  asm volatile("" ::: "memory");
+
 __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char Ks[KTILE * DH * 2];
-  __shared__ __attribute__((aligned(16))) char Vt[DH * KTILE * 2];
+  // one array per stage and operand: the compiler tracks loads-to-LDS per array, so reads of the stage in
+  // use do not wait for the copies in flight to the other
+  __shared__ __attribute__((aligned(1024))) char K0[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char K1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char V0[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char V1[kTileBytes];
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lh = lane >> 5;
   const int tile = blockIdx.x, kvh = blockIdx.y;
   const int n0 = tile * a.npt;
@@ -81,77 +112,57 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   const unsigned long long* rm = a.rowmask + (size_t)(row_ok ? node : 0) * a.W64;
   const unsigned rowB = (unsigned)a.Hkv * DH * 2;  // bytes between consecutive key rows
 
-  // ---- staging registers for the next tile ------------------------------------------------------------
-  // K: lane fetches the 16-byte chunk (tid & 15) of keys (tid >> 4) + 16 i.  V: wave w fetches, for
-  // the 16 key slots it transposes, the 4-byte column pair `lane` of each.  Slots past the end of
-  // the key list re-read the last valid key (finite data); the mask keeps them out of the softmax.
-  u32x4 rk[4];
-  unsigned rv[2][8];
+  // ---- copies: global -> LDS ---------------------------------------------------------------------------
+  // Copy instruction t (0..3) of wave w fills tile rows 16 w + 4 t .. + 3 (1 KB of LDS): lane l supplies
+  // row 16 w + 4 t + l / 16, LDS chunk position l % 16, i.e. the chunk that the swizzle puts there.
+  // Slots past the end of the key list re-read the last valid key (finite data); the mask keeps them
+  // out of the softmax.
+  const __amdgpu_buffer_rsrc_t kpre = make_rsrc(a.k_prefix), vpre = make_rsrc(a.v_prefix);
+  const __amdgpu_buffer_rsrc_t ktre = make_rsrc(a.k_tree), vtre = make_rsrc(a.v_tree);
+  const int crow = 16 * wave + (lane >> 4);               // + 4 t
+  const unsigned colB = (unsigned)kvh * DH * 2;
+  unsigned kcol[4];                                        // byte offset of the K chunk inside the row, per t
+#pragma unroll
+  for (int t = 0; t < 4; ++t) kcol[t] = colB + ((((unsigned)lane & 15u) ^ ((4u * t + ((unsigned)lane >> 4)) & 15u)) << 4);
+  const unsigned vcol = colB + ((((unsigned)lane & 15u) ^ ((((unsigned)lane >> 4) & 3u) << 2)) << 4);
+  const int cdst = wave * 4096;
   unsigned long long rmask = 0ull;
-  const unsigned kcol = (unsigned)kvh * DH * 2 + (tid & 15) * 16;
-  const unsigned vcol = (unsigned)kvh * DH * 2 + lane * 4;
-  auto fetch_prefix = [&](int t) {
-    const int base = t * KTILE;
-    const int last = a.P - 1;
-    const char* kb = reinterpret_cast<const char*>(a.k_prefix);
-    const char* vb = reinterpret_cast<const char*>(a.v_prefix);
+
+#define SX_COPY_TILE(KS_, VS_, KRES_, VRES_, ROWOFF_)                                                              \
+  _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                                  \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(KRES_, (lds_void_ptr)(KS_ + cdst + t * 1024), 16, ROWOFF_[t] + kcol[t], 0, 0, \
+                                             0);                                                                   \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(VRES_, (lds_void_ptr)(VS_ + cdst + t * 1024), 16, ROWOFF_[t] + vcol, 0, 0, 0); \
+  }
+// starts the copies of tile T_ (prefix tiles first, then tree tiles) into stage (KS_, VS_) and sets rmask
+#define SX_FETCH(T_, KS_, VS_)                                                                                     \
+  if ((T_) < nPre) {                                                                                               \
+    const int base = (T_) * KTILE, last = a.P - 1;                                                                 \
+    unsigned roff[4];                                                                                              \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) roff[t] = (unsigned)min(base + crow + 4 * t, last) * rowB;       \
+    SX_COPY_TILE(KS_, VS_, kpre, vpre, roff)                                                                       \
+    const int count = min(KTILE, a.P - base);                                                                      \
+    rmask = count == KTILE ? ~0ull : ((1ull << count) - 1ull);                                                     \
+  } else {                                                                                                         \
+    const int base = ((T_) - nPre) * KTILE, last = cnt - 1;                                                        \
+    unsigned roff[4];                                                                                              \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) roff[t] = (unsigned)kl[min(base + crow + 4 * t, last)] * rowB;   \
+    SX_COPY_TILE(KS_, VS_, ktre, vtre, roff)                                                                       \
+    rmask = row_ok ? rm[(T_) - nPre] : 0ull;                                                                       \
+  }
+
+  // ---- V^T fragment addresses (transpose read) -----------------------------------------------------------
+  // Fragment (db, s4) for lane l: d = 32 db + l32, the 8 keys 16 s4 + 4 lh + {0..3} and + 8 (the order
+  // in which this lane's probabilities sit in the P operand).  Lane s = l % 16 of the 16-lane group
+  // q = l / 16 addresses key 16 s4 + 8 r + 4 lh + s / 4, d = 32 db + 16 (q % 2) + 4 (s % 4) .. + 3.
+  const int vs = lane & 15, vq = lane >> 4;
+  const int vkey = 4 * lh + (vs >> 2);                             // + 16 s4 + 8 r
+  const int vbase = vkey * (DH * 2) + 8 * (vs & 1);                // row and the 8-byte half of the chunk
+  const int vchunk = 2 * (vq & 1) + ((vs & 3) >> 1);               // + 4 db
+  const int vswz = (vkey & 3) << 2;
+  int vpc[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = min(base + (tid >> 4) + 16 * i, last);
-      rk[i] = *reinterpret_cast<const u32x4*>(kb + (size_t)((unsigned)row * rowB + kcol));
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int row = min(base + 16 * wave + (j >> 2) * 8 + 4 * h + (j & 3), last);
-        rv[h][j] = *reinterpret_cast<const unsigned*>(vb + (size_t)((unsigned)row * rowB + vcol));
-      }
-    const int count = min(KTILE, a.P - base);
-    rmask = count == KTILE ? ~0ull : ((1ull << count) - 1ull);
-  };
-  auto fetch_tree = [&](int t) {
-    const int base = t * KTILE;
-    const int last = cnt - 1;
-    const char* kb = reinterpret_cast<const char*>(a.k_tree);
-    const char* vb = reinterpret_cast<const char*>(a.v_tree);
-    int krow[4], vrow[2][8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) krow[i] = kl[min(base + (tid >> 4) + 16 * i, last)];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) vrow[h][j] = kl[min(base + 16 * wave + (j >> 2) * 8 + 4 * h + (j & 3), last)];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      rk[i] = *reinterpret_cast<const u32x4*>(kb + (size_t)((unsigned)krow[i] * rowB + kcol));
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        rv[h][j] = *reinterpret_cast<const unsigned*>(vb + (size_t)((unsigned)vrow[h][j] * rowB + vcol));
-    rmask = row_ok ? rm[t] : 0ull;
-  };
-  auto fetch = [&](int t) {
-    if (t < nPre) fetch_prefix(t);
-    else fetch_tree(t - nPre);
-  };
-  auto stash = [&]() {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(Ks + ks_off((tid >> 4) + 16 * i, tid & 15)) = rk[i];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      u32x4 ev, od;  // d = 2*lane (low halves) and d = 2*lane+1 (high halves), 8 key slots each
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const unsigned w0 = rv[h][2 * p], w1 = rv[h][2 * p + 1];
-        ev[p] = (w0 & 0xFFFFu) | (w1 << 16);
-        od[p] = (w0 >> 16) | (w1 & 0xFFFF0000u);
-      }
-      *reinterpret_cast<u32x4*>(Vt + vt_off(2 * lane, 2 * wave + h)) = ev;
-      *reinterpret_cast<u32x4*>(Vt + vt_off(2 * lane + 1, 2 * wave + h)) = od;
-    }
-  };
+  for (int db = 0; db < 4; ++db) vpc[db] = vbase + (((4 * db + vchunk) ^ vswz) << 4);
 
   // ---- running state of this lane's row ----------------------------------------------------------
   // m_ref is the reference the exponentials are taken against.  It follows the running maximum
@@ -168,85 +179,90 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
 
-  const int nTiles = nPre + nTree;
-  if (nTiles > 0) fetch(0);
-  for (int t = 0; t < nTiles; ++t) {
-    __syncthreads();  // everyone is done reading the previous tile
-    stash();
-    const unsigned long long mask = rmask >> (4 * lh);
-    __syncthreads();
-    if (t + 1 < nTiles) fetch(t + 1);
-
-    // ---- S^T = K Q^T : st[kb][e] = score(key 32kb + 8(e/4) + 4lh + e%4, this lane's row) --------------
-    f32x16 st[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) st[kb][e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + ks_off(32 * kb + l32, 2 * ks + lh));
-        st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);
-      }
-    }
-    // ---- online softmax for this row ------------------------------------------------------------
-    float mx = NEG_INF;
-    if (mask != (~0ull >> (4 * lh))) {  // some key slots are not this row's: only tail and tree tiles
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int bit = 32 * kb + 8 * (e >> 2) + (e & 3);  // + 4*lh, already shifted out of `mask`
-          st[kb][e] = ((mask >> bit) & 1ull) ? st[kb][e] : NEG_INF;
-        }
-    }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float alpha = 1.0f;
-    if (mx > m_ref + slack_raw) {  // also taken on the first tile (m_ref = -inf)
-      alpha = __builtin_amdgcn_exp2f((m_ref - mx) * c2);
-      m_ref = mx;
-    }
-    const float m_use = (m_ref == NEG_INF) ? 0.f : m_ref;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
-      l_run *= alpha;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[i][e] *= alpha;
-    }
-    float psum = 0.f;
-    bf16x8 phi[4], plo[4];
-    const float mc = m_use * c2;
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      u32x4 hi4, lo4;
-#pragma unroll
-      for (int jp = 0; jp < 4; ++jp) {
-        const float p0 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp] * c2 - mc);
-        const float p1 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp + 1] * c2 - mc);
-        psum += p0 + p1;
-        const unsigned h2 = cvt_pk_bf16(p0, p1);
-        hi4[jp] = h2;
-        lo4[jp] = cvt_pk_bf16(p0 - __uint_as_float(h2 << 16), p1 - __uint_as_float(h2 & 0xFFFF0000u));
-      }
-      phi[s4] = __builtin_bit_cast(bf16x8, hi4);
-      plo[s4] = __builtin_bit_cast(bf16x8, lo4);
-    }
-    l_run += psum;
-    // ---- O^T += V^T P^T : oacc[db][e] = out(d = 32db + 8(e/4) + 4lh + e%4, this lane's row) ------------
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vt + vt_off(32 * db + l32, 2 * s4 + lh));
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, phi[s4], oacc[db], 0, 0, 0);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, plo[s4], oacc[db], 0, 0, 0);
-      }
+// one key tile out of stage (KS_, VS_); `mask` = which of its 64 slots belong to this lane's row (bits of
+// the lane half already shifted out)
+#define SX_TILE(KS_, VS_)                                                                                          \
+  {                                                                                                                \
+    /* ---- S^T = K Q^T : st[kb][e] = score(key 32kb + 8(e/4) + 4lh + e%4, this lane's row) ---- */               \
+    f32x16 st[2];                                                                                                  \
+    _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                             \
+      _Pragma("unroll") for (int e = 0; e < 16; ++e) st[kb][e] = 0.f;                                              \
+      _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {                                                           \
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(KS_ + ks_off(32 * kb + l32, 2 * ks + lh));              \
+        st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);                             \
+      }                                                                                                            \
+    }                                                                                                              \
+    /* ---- online softmax for this row ---- */                                                                    \
+    float mx = NEG_INF;                                                                                            \
+    if (mask != (~0ull >> (4 * lh))) { /* some key slots are not this row's: only tail and tree tiles */           \
+      _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int e = 0; e < 16; ++e) {            \
+        const int bit = 32 * kb + 8 * (e >> 2) + (e & 3); /* + 4*lh, already shifted out of `mask` */              \
+        st[kb][e] = ((mask >> bit) & 1ull) ? st[kb][e] : NEG_INF;                                                  \
+      }                                                                                                            \
+    }                                                                                                              \
+    _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int e = 0; e < 16; ++e)                \
+        mx = fmaxf(mx, st[kb][e]);                                                                                 \
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                        \
+    float alpha = 1.0f;                                                                                            \
+    if (mx > m_ref + slack_raw) { /* also taken on the first tile (m_ref = -inf) */                                \
+      alpha = __builtin_amdgcn_exp2f((m_ref - mx) * c2);                                                           \
+      m_ref = mx;                                                                                                  \
+    }                                                                                                              \
+    const float m_use = (m_ref == NEG_INF) ? 0.f : m_ref;                                                          \
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {                                                      \
+      l_run *= alpha;                                                                                              \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int e = 0; e < 16; ++e)                 \
+          oacc[i][e] *= alpha;                                                                                     \
+    }                                                                                                              \
+    float psum = 0.f;                                                                                              \
+    bf16x8 phi[4], plo[4];                                                                                         \
+    const float mc = m_use * c2;                                                                                   \
+    _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                                             \
+      u32x4 hi4, lo4;                                                                                              \
+      _Pragma("unroll") for (int jp = 0; jp < 4; ++jp) {                                                           \
+        const float p0 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp] * c2 - mc);                     \
+        const float p1 = __builtin_amdgcn_exp2f(st[s4 >> 1][8 * (s4 & 1) + 2 * jp + 1] * c2 - mc);                 \
+        psum += p0 + p1;                                                                                           \
+        const unsigned h2 = cvt_pk_bf16(p0, p1);                                                                   \
+        hi4[jp] = h2;                                                                                              \
+        lo4[jp] = cvt_pk_bf16(p0 - __uint_as_float(h2 << 16), p1 - __uint_as_float(h2 & 0xFFFF0000u));             \
+      }                                                                                                            \
+      phi[s4] = __builtin_bit_cast(bf16x8, hi4);                                                                   \
+      plo[s4] = __builtin_bit_cast(bf16x8, lo4);                                                                   \
+    }                                                                                                              \
+    l_run += psum;                                                                                                 \
+    /* ---- O^T += V^T P^T : oacc[db][e] = out(d = 32db + 8(e/4) + 4lh + e%4, this lane's row) ---- */             \
+    _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) _Pragma("unroll") for (int db = 0; db < 4; ++db) {            \
+      const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(VS_ + s4 * 4096 + vpc[db]));        \
+      const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(VS_ + s4 * 4096 + 2048 + vpc[db])); \
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));       \
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, phi[s4], oacc[db], 0, 0, 0);                          \
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, plo[s4], oacc[db], 0, 0, 0);                          \
+    }                                                                                                              \
   }
+
+  // Tile t lives in stage t % 2.  Top of an iteration: wait for this wave's copies of tile t, barrier
+  // (everybody's are in, and everybody is done with tile t-1, whose stage the copies of tile t+1 go to).
+  const int nTiles = nPre + nTree;
+  if (nTiles > 0) { SX_FETCH(0, K0, V0) }
+  for (int t = 0; t < nTiles; t += 2) {
+    {
+      SX_WAIT_BARRIER()
+      const unsigned long long mask = rmask >> (4 * lh);
+      if (t + 1 < nTiles) { SX_FETCH(t + 1, K1, V1) }
+      SX_TILE(K0, V0)
+    }
+    if (t + 1 < nTiles) {
+      SX_WAIT_BARRIER()
+      const unsigned long long mask = rmask >> (4 * lh);
+      if (t + 2 < nTiles) { SX_FETCH(t + 2, K0, V0) }
+      SX_TILE(K1, V1)
+    }
+  }
+#undef SX_TILE
+#undef SX_FETCH
+#undef SX_COPY_TILE
+#undef SX_WAIT_BARRIER
 
   // ---- normalise and store -------------------------------------------------------------------------
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -274,6 +290,8 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
                              hipStream_t st) {
   const int G = Hq / Hkv;
   if (Hq % Hkv != 0 || !(G == 1 || G == 2 || G == 4 || G == 8)) return SX_ERR_SHAPE;
+  // the copies address rows with 32-bit byte offsets from the start of each K/V array
+  if ((unsigned long long)(P > T ? P : T) * Hkv * DH * 2 >= (1ull << 32)) return SX_ERR_SHAPE;
   AttnArgs a;
   a.q = static_cast<const unsigned short*>(q);
   a.k_tree = static_cast<const unsigned short*>(k_tree);
