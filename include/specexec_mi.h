@@ -117,6 +117,20 @@ int sx_verify_tree_cached(const sx_weights *w, const void *prefix_k, const void 
                           const int32_t *parent_idx, int32_t T, float *logits_out, void *tree_k_out,
                           void *tree_v_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same forward for the nodes first .. T-1 only, of a tree whose nodes 0 .. first-1 went through an
+ * earlier call (Alg. 2: "forward(batch, theta_draft) ... attend to past tokens": a tree that grows
+ * by a batch of nodes per step).  tree_k_out / tree_v_out are device [L][tree_capacity][Hkv][Dh]
+ * (tree_capacity >= T) and persistent across calls: rows [0, first) of every layer are read as keys and
+ * values, rows [first, T) are written.  They are required when first > 0.  tree_tokens and parent_idx
+ * describe all T nodes (indices are global); logits_out is device float [T - first][V], row i for node
+ * first + i.  Workspace as for sx_verify_tree(P, T).  sx_verify_tree_cached is this call with first = 0
+ * and tree_capacity = T. */
+int sx_verify_tree_range(const sx_weights *w, const void *prefix_k, const void *prefix_v,
+                         int32_t capacity, int32_t P, const int32_t *tree_tokens,
+                         const int32_t *parent_idx, int32_t T, int32_t first, float *logits_out,
+                         void *tree_k_out, void *tree_v_out, int32_t tree_capacity, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * sx_accept_walk -- Alg. 1, main loop: p_target := cache[x]; x_next ~ sample(p_target).
  *

@@ -8,7 +8,7 @@ import os
 import torch
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
-EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_commit_kv",
+EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
            "sx_specexec_round_workspace", "sx_specexec_round", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
@@ -53,6 +53,8 @@ def _load():
     L.sx_accept_walk_workspace.restype = sz
     L.sx_verify_tree_cached.restype = C.c_int
     L.sx_verify_tree_cached.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.sx_verify_tree_range.restype = C.c_int
+    L.sx_verify_tree_range.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i32, vp, sz, vp]
     L.sx_commit_kv.restype = C.c_int
     L.sx_commit_kv.argtypes = [C.POINTER(_Cfg), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp]
     L.sx_specexec_round_workspace.restype = sz
@@ -169,6 +171,24 @@ def verify_tree(weights: ModelWeights, prefix_k, prefix_v, tree_tokens, parent_i
                                    _ptr(parent_idx), T, _ptr(logits_out), _ptr(tree_k_out), _ptr(tree_v_out),
                                    _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "sx_verify_tree")
+    return logits_out, workspace
+
+
+def verify_tree_range(weights: ModelWeights, prefix_k, prefix_v, P: int, tree_tokens, parent_idx, first: int, tree_k,
+                      tree_v, logits_out=None, workspace=None, stream=None):
+    """sx_verify_tree_range: forward of nodes first .. T-1 of a tree whose earlier nodes' K/V are in tree_k/tree_v
+    ([L][tree_capacity][Hkv][Dh], persistent).  Returns (logits [T - first][V], workspace)."""
+    cfg = weights.cfg
+    T = int(tree_tokens.numel())
+    capacity = 0 if prefix_k is None else int(prefix_k.shape[1])
+    if logits_out is None:
+        logits_out = torch.empty((T - first, cfg.vocab), dtype=torch.float32, device=weights.device)
+    if workspace is None:
+        workspace = _workspace(verify_tree_workspace(cfg, P, T), weights.device)
+    rc = lib.sx_verify_tree_range(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), capacity, P, _ptr(tree_tokens),
+                                  _ptr(parent_idx), T, first, _ptr(logits_out), _ptr(tree_k), _ptr(tree_v),
+                                  int(tree_k.shape[1]), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "sx_verify_tree_range")
     return logits_out, workspace
 
 

@@ -14,7 +14,8 @@ int sx_launch_rope_table(const int32_t* pos, int T, int P, int head_dim, float r
 // Per query tile of `nodes_per_tile` consecutive nodes: the sorted union of their ancestors
 // (klist[tile][0..kcnt[tile])) and, per node, a bitmask over positions of that list
 // (rowmask[node][w], bit b of word w <=> list position 64w+b is an ancestor-or-self of node).
-int sx_launch_qtile_prep(const int32_t* par_s, int T, int nodes_per_tile, int32_t* klist, int32_t* kcnt,
+// The tiles cover the query nodes first .. T-1 (rowmask rows indexed by node - first); list entries are node ids.
+int sx_launch_qtile_prep(const int32_t* par_s, int T, int nodes_per_tile, int first, int32_t* klist, int32_t* kcnt,
                          unsigned long long* rowmask, hipStream_t st);
 
 // ---- elementwise (elementwise.hip) -----------------------------------------------------------------
@@ -30,9 +31,10 @@ int sx_launch_swiglu_f32(const float* g, const float* u, float* a, size_t n, hip
 // Y[M][N] (+)= X[M][K] W[N][K]^T, all fp32, ldy = row stride of Y.
 int sx_launch_gemm_f32(const float* X, const float* W, float* Y, int M, int N, int K, int ldy, bool accumulate,
                        hipStream_t st);
+// q and out hold the query nodes first .. T-1 (row = node - first); k_tree / v_tree hold all T nodes.
 int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_tree, const float* k_prefix,
-                            const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int P, int Hq,
-                            int Hkv, int Dh, float* out, hipStream_t st);
+                            const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int first, int P,
+                            int Hq, int Hkv, int Dh, float* out, hipStream_t st);
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------------
 enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2, SX_GEMM_QKV_ROPE = 3 };
@@ -50,9 +52,10 @@ int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, 
                                  size_t split_ws_bytes, hipStream_t st);
 // n int32 zeros (a fill kernel: safe to capture in a graph, unlike a memset node)
 int sx_launch_zero_i32(int32_t* p, int n, hipStream_t st);
+// q and out hold Tq query nodes; k_tree / v_tree hold all T nodes of the tree; klist rows have stride T.
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
-                             const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,
+                             const unsigned long long* rowmask, int T, int Tq, int P, int Hq, int Hkv, void* out,
                              hipStream_t st);
 static inline int sx_attn_nodes_per_tile(int Hq, int Hkv) { return 128 / (Hq / Hkv); }
 

@@ -57,10 +57,10 @@ constexpr int kAttnThreads = 128;
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k_tree, const float* __restrict__ v_tree,
     const float* __restrict__ k_prefix, const float* __restrict__ v_prefix, const int* __restrict__ par_s,
-    const int* __restrict__ depth, int P, int Hq, int Hkv, int Dh, float* __restrict__ out) {
+    const int* __restrict__ depth, int first, int P, int Hq, int Hkv, int Dh, float* __restrict__ out) {
   extern __shared__ float lds[];
   __shared__ float red[2];
-  const int node = blockIdx.x, h = blockIdx.y;
+  const int node = first + blockIdx.x, h = blockIdx.y;
   const int kv = h / (Hq / Hkv);
   const int na = depth[node] + 1;
   const int nk = P + na;
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_f32_kernel(
     }
   }
   __syncthreads();
-  const float* qv = q + ((size_t)node * Hq + h) * Dh;
+  const float* qv = q + ((size_t)blockIdx.x * Hq + h) * Dh;
   const float scale = 1.0f / sqrtf((float)Dh);
   float mx = -__builtin_huge_valf();
   for (int j = tid; j < nk; j += kAttnThreads) {
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_f32_kernel(
       const float* vr = (j < P) ? v_prefix + ((size_t)j * Hkv + kv) * Dh : v_tree + ((size_t)anc[j - P] * Hkv + kv) * Dh;
       o += sc[j] * vr[c];
     }
-    out[((size_t)node * Hq + h) * Dh + c] = o * inv;
+    out[((size_t)blockIdx.x * Hq + h) * Dh + c] = o * inv;
   }
 }
 
@@ -116,14 +116,14 @@ int sx_launch_gemm_f32(const float* X, const float* W, float* Y, int M, int N, i
 }
 
 int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_tree, const float* k_prefix,
-                            const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int P, int Hq,
-                            int Hkv, int Dh, float* out, hipStream_t st) {
+                            const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int first, int P,
+                            int Hq, int Hkv, int Dh, float* out, hipStream_t st) {
   // worst case: a chain, depth T-1
   const size_t shmem = (size_t)(P + 2 * T) * sizeof(float);
   if (shmem > 60 * 1024) return SX_ERR_SHAPE;
-  dim3 grid(T, Hq);
-  tree_attn_f32_kernel<<<grid, kAttnThreads, shmem, st>>>(q, k_tree, v_tree, k_prefix, v_prefix, par_s, depth, P, Hq,
-                                                          Hkv, Dh, out);
+  dim3 grid(T - first, Hq);
+  tree_attn_f32_kernel<<<grid, kAttnThreads, shmem, st>>>(q, k_tree, v_tree, k_prefix, v_prefix, par_s, depth, first, P,
+                                                          Hq, Hkv, Dh, out);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

@@ -48,7 +48,7 @@ struct AttnArgs {
   const int* kcnt;                 // [tiles]
   const unsigned long long* rowmask;  // [T][W64]
   unsigned short* out;             // [T][Hq][128]
-  int T, P, Hq, Hkv, G, npt, W64;
+  int T, Tq, P, Hq, Hkv, G, npt, W64;  // T: nodes of the tree (klist stride); Tq: query nodes in q/out
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   const int r = wave * 32 + l32;
   const int node = n0 + r / a.G;
   const int head = kvh * a.G + r % a.G;
-  const bool row_ok = node < a.T;
+  const bool row_ok = node < a.Tq;
   bf16x8 qf[8];
   {
     const unsigned short* qp = a.q + ((size_t)(row_ok ? node : 0) * a.Hq + head) * DH + lh * 8;
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
 
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
-                             const unsigned long long* rowmask, int T, int P, int Hq, int Hkv, void* out,
+                             const unsigned long long* rowmask, int T, int Tq, int P, int Hq, int Hkv, void* out,
                              hipStream_t st) {
   const int G = Hq / Hkv;
   if (Hq % Hkv != 0 || !(G == 1 || G == 2 || G == 4 || G == 8)) return SX_ERR_SHAPE;
@@ -303,13 +303,14 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
   a.rowmask = rowmask;
   a.out = static_cast<unsigned short*>(out);
   a.T = T;
+  a.Tq = Tq;
   a.P = P;
   a.Hq = Hq;
   a.Hkv = Hkv;
   a.G = G;
   a.npt = QROWS / G;
   a.W64 = (T + 63) / 64;
-  dim3 grid((T + a.npt - 1) / a.npt, Hkv);
+  dim3 grid((Tq + a.npt - 1) / a.npt, Hkv);
   tree_attn_bf16_kernel<<<grid, kThreads, 0, st>>>(a);
   SX_LAUNCH_CHECK();
   return SX_OK;

@@ -55,7 +55,9 @@ __global__ void rope_table_kernel(const int* __restrict__ depth, int T, int P, i
 
 // One workgroup per query tile.
 constexpr int kQtThreads = 256;
-__global__ __launch_bounds__(kQtThreads) void qtile_prep_kernel(const int* __restrict__ par_s, int T, int npt,
+// Tiles cover the query nodes first, first + 1, ..., T - 1 (first > 0: the earlier nodes were processed by
+// a previous call and only serve as keys); rowmask rows are indexed by node - first.
+__global__ __launch_bounds__(kQtThreads) void qtile_prep_kernel(const int* __restrict__ par_s, int T, int npt, int first,
                                                                 int* __restrict__ klist, int* __restrict__ kcnt,
                                                                 unsigned long long* __restrict__ rowmask) {
   extern __shared__ unsigned int lds[];
@@ -65,7 +67,7 @@ __global__ __launch_bounds__(kQtThreads) void qtile_prep_kernel(const int* __res
   unsigned int* pre = lds + W;      // [W+1] exclusive prefix of popcounts
   const int tid = threadIdx.x;
   const int tile = blockIdx.x;
-  const int n0 = tile * npt;
+  const int n0 = first + tile * npt;
   for (int w = tid; w < W; w += kQtThreads) bm[w] = 0u;
   __syncthreads();
   if (tid < npt && n0 + tid < T) {
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(kQtThreads) void qtile_prep_kernel(const int* __res
   // per-node masks over list positions; each row is touched by its own lane only
   const int nw = (cnt + 63) / 64;
   if (tid < npt && n0 + tid < T) {
-    unsigned long long* rm = rowmask + (size_t)(n0 + tid) * (size_t)W64;
+    unsigned long long* rm = rowmask + (size_t)(n0 + tid - first) * (size_t)W64;
     for (int w = 0; w < nw; ++w) rm[w] = 0ull;
     for (int j = n0 + tid; j >= 0; j = par_s[j]) {
       const int pos = (int)pre[j >> 5] + __popc(bm[j >> 5] & ((1u << (j & 31)) - 1u));
@@ -120,12 +122,12 @@ int sx_launch_rope_table(const int32_t* pos, int T, int P, int head_dim, float r
   return SX_OK;
 }
 
-int sx_launch_qtile_prep(const int32_t* par_s, int T, int nodes_per_tile, int32_t* klist, int32_t* kcnt,
+int sx_launch_qtile_prep(const int32_t* par_s, int T, int nodes_per_tile, int first, int32_t* klist, int32_t* kcnt,
                          unsigned long long* rowmask, hipStream_t st) {
-  const int tiles = (T + nodes_per_tile - 1) / nodes_per_tile;
+  const int tiles = (T - first + nodes_per_tile - 1) / nodes_per_tile;
   const int W = (T + 31) / 32;
   qtile_prep_kernel<<<tiles, kQtThreads, (size_t)(2 * W + 1) * sizeof(unsigned int), st>>>(par_s, T, nodes_per_tile,
-                                                                                           klist, kcnt, rowmask);
+                                                                                           first, klist, kcnt, rowmask);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

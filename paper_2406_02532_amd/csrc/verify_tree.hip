@@ -121,7 +121,17 @@ extern "C" int sx_verify_tree_cached(const sx_weights* w, const void* prefix_k, 
                                      int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T,
                                      float* logits_out, void* tree_k_out, void* tree_v_out, void* workspace,
                                      size_t workspace_bytes, void* stream) {
-  if (capacity < P) return SX_ERR_SHAPE;
+  return sx_verify_tree_range(w, prefix_k, prefix_v, capacity, P, tree_tokens, parent_idx, T, 0, logits_out, tree_k_out,
+                              tree_v_out, T, workspace, workspace_bytes, stream);
+}
+
+extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t capacity,
+                                    int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T,
+                                    int32_t first, float* logits_out, void* tree_k_out, void* tree_v_out,
+                                    int32_t tree_capacity, void* workspace, size_t workspace_bytes, void* stream) {
+  if (capacity < P || first < 0 || first >= T || tree_capacity < T) return SX_ERR_SHAPE;
+  if (first > 0 && (!tree_k_out || !tree_v_out)) return SX_ERR_NULL;  // the earlier nodes' K/V live there
+  const int n = T - first;  // rows of this call: nodes first .. T-1
   if (!w || !tree_tokens || !parent_idx || !logits_out || !w->embed || !w->layers || !w->final_norm || !w->lm_head)
     return SX_ERR_NULL;
   const sx_model_cfg& c = w->cfg;
@@ -147,64 +157,68 @@ extern "C" int sx_verify_tree_cached(const sx_weights* w, const void* prefix_k, 
   SX_TIMED(SX_K_PREP, sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth,
                                           L.rope_cs, status, st));
   if (bf)
-    SX_TIMED(SX_K_PREP,
-             sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), L.klist, L.kcnt, L.rowmask, st));
-  SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s, T, d, L.h, st));
+    SX_TIMED(SX_K_PREP, sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), first, L.klist, L.kcnt,
+                                             L.rowmask, st));
+  SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s + first, n, d, L.h, st));
+  const float2* rope_cs = L.rope_cs + (size_t)first * (Dh / 2);  // rows of this call's nodes
   if (bf && Dh == 128) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(L.qkv), 256, st));  // K-split counters
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
-    const size_t kv_layer = (size_t)l * T * Nkv * es, pre_layer = (size_t)l * capacity * Nkv * es;
-    void* tk = tree_k_out ? static_cast<char*>(tree_k_out) + kv_layer : L.tk;
-    void* tv = tree_v_out ? static_cast<char*>(tree_v_out) + kv_layer : L.tv;
+    const size_t kv_layer = (size_t)l * tree_capacity * Nkv * es, pre_layer = (size_t)l * capacity * Nkv * es;
+    // this layer's K/V of all tree nodes (keys of the attention) and where this call's nodes go in them
+    char* tkb = tree_k_out ? static_cast<char*>(tree_k_out) + kv_layer : static_cast<char*>(L.tk);
+    char* tvb = tree_v_out ? static_cast<char*>(tree_v_out) + kv_layer : static_cast<char*>(L.tv);
+    void* tk = tkb + (size_t)first * Nkv * es;
+    void* tv = tvb + (size_t)first * Nkv * es;
     const void* pk = P > 0 ? static_cast<const char*>(prefix_k) + pre_layer : nullptr;
     const void* pv = P > 0 ? static_cast<const char*>(prefix_v) + pre_layer : nullptr;
 
-    SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+    SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
     const bool fused_rope = bf && Dh == 128;  // the GEMM's epilogue rotates and splits into heads
     if (fused_rope) {
       SX_TIMED(SX_K_GEMM_QKV,
-               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, L.rope_cs, L.q, tk, tv, T, d, L.qkv,
+               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, rope_cs, L.q, tk, tv, n, d, L.qkv,
                                             L.qkv_bytes, st));
     } else if (bf) {
       SX_TIMED(SX_K_GEMM_QKV,
-               sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, T, d, SX_GEMM_STORE, st));
+               sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, n, d, SX_GEMM_STORE, st));
     } else {
       const int ld = Nq + 2 * Nkv;
       const float* x = static_cast<const float*>(L.x);
-      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wq, L.qkv, T, Nq, d, ld, false, st));
-      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wk, L.qkv + Nq, T, Nkv, d, ld, false, st));
-      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wv, L.qkv + Nq + Nkv, T, Nkv, d, ld, false, st));
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wq, L.qkv, n, Nq, d, ld, false, st));
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wk, L.qkv + Nq, n, Nkv, d, ld, false, st));
+      SX_TRY(sx_launch_gemm_f32(x, (const float*)lw.wv, L.qkv + Nq + Nkv, n, Nkv, d, ld, false, st));
     }
     if (!fused_rope)
-      SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, L.rope_cs, T, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
+      SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, rope_cs, n, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
     if (bf) {
-      SX_TIMED(SX_K_ATTN,
-               sx_launch_tree_attn_bf16(L.q, tk, tv, pk, pv, L.klist, L.kcnt, L.rowmask, T, P, Hq, Hkv, L.o, st));
+      SX_TIMED(SX_K_ATTN, sx_launch_tree_attn_bf16(L.q, tkb, tvb, pk, pv, L.klist, L.kcnt, L.rowmask, T, n, P, Hq, Hkv,
+                                                   L.o, st));
       SX_TIMED(SX_K_GEMM_O,
-               sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, T, Nq, SX_GEMM_RESIDUAL, st));
-      SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+               sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, n, Nq, SX_GEMM_RESIDUAL, st));
+      SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
       SX_TIMED(SX_K_GEMM_GATEUP,
-               sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, T, d, SX_GEMM_SWIGLU, st));
+               sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, n, d, SX_GEMM_SWIGLU, st));
       SX_TIMED(SX_K_GEMM_DOWN,
-               sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, T, F, SX_GEMM_RESIDUAL, st));
+               sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, n, F, SX_GEMM_RESIDUAL, st));
     } else {
-      SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tk, (const float*)tv, (const float*)pk,
-                                     (const float*)pv, L.par_s, L.depth, T, P, Hq, Hkv, Dh, (float*)L.o, st));
-      SX_TRY(sx_launch_gemm_f32((const float*)L.o, (const float*)lw.wo, L.h, T, d, Nq, d, true, st));
-      SX_TRY(sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, T, d, c.rms_eps, L.x, st));
-      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_gate, L.gate, T, F, d, F, false, st));
-      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_up, L.up, T, F, d, F, false, st));
-      SX_TRY(sx_launch_swiglu_f32(L.gate, L.up, (float*)L.act, (size_t)T * F, st));
-      SX_TRY(sx_launch_gemm_f32((const float*)L.act, (const float*)lw.w_down, L.h, T, d, F, d, true, st));
+      SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tkb, (const float*)tvb, (const float*)pk,
+                                     (const float*)pv, L.par_s, L.depth, T, first, P, Hq, Hkv, Dh, (float*)L.o, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.o, (const float*)lw.wo, L.h, n, d, Nq, d, true, st));
+      SX_TRY(sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_gate, L.gate, n, F, d, F, false, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)lw.w_up, L.up, n, F, d, F, false, st));
+      SX_TRY(sx_launch_swiglu_f32(L.gate, L.up, (float*)L.act, (size_t)n * F, st));
+      SX_TRY(sx_launch_gemm_f32((const float*)L.act, (const float*)lw.w_down, L.h, n, d, F, d, true, st));
     }
   }
-  SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, T, d, c.rms_eps, L.x, st));
+  SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, n, d, c.rms_eps, L.x, st));
   if (bf)
     SX_TIMED(SX_K_GEMM_LMHEAD,
-             sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, T, d, SX_GEMM_STORE, st));
+             sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, n, d, SX_GEMM_STORE, st));
   else
-    SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, T, V, d, V, false, st));
+    SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, n, V, d, V, false, st));
   return SX_OK;
 }
 
@@ -323,8 +337,8 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
   hipStream_t st = (hipStream_t)stream;
   SX_TRY(sx_launch_tree_prep(nullptr, parent_idx, T, 1, P, 128, 10000.f, L.tok_s, L.par_s, L.depth, L.cs,
                              static_cast<int32_t*>(workspace), st));
-  SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, L.klist, L.kcnt, L.rowmask, st));
-  return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, P, n_q_heads,
+  SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, 0, L.klist, L.kcnt, L.rowmask, st));
+  return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, T, P, n_q_heads,
                                   n_kv_heads, out, st);
 }
 

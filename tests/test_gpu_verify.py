@@ -219,6 +219,62 @@ def test_c1_rounds_with_kv_commit_equal_sequential_sampling(sx, c1):
     assert checked >= 4
 
 
+def test_c1_tree_verified_in_batches_of_nodes_matches_oracle(sx, c1):
+    """Alg. 2's forward over a growing tree: nodes are verified a batch at a time (sx_verify_tree_range), each
+    batch attending to the prefix and to ancestors from earlier batches through the persistent tree K/V.
+    Every row must be the oracle's row for that node, whatever the batch boundaries."""
+    cfg, w, wn, pk, pv = c1
+    P = pk.shape[1]
+    mw = sx.ModelWeights(cfg, weights_to(w, dev()))
+    tok, par, _ = wl.gen_best_first_tree(48, 4, cfg.vocab, seed=9, max_depth=12)
+    T = len(tok)
+    ref = oracle.verify_tree(cfg, wn, pk, pv, tok, par)
+    pkd, pvd = to_dev(torch.as_tensor(pk), torch.float32), to_dev(torch.as_tensor(pv), torch.float32)
+    for bounds in ([0, T], [0, 1, T], [0, 5, 6, 23, 40, T]):
+        tree_k = torch.zeros((cfg.n_layers, T + 3, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device=dev())
+        tree_v = torch.zeros_like(tree_k)
+        rows = []
+        for lo, hi in zip(bounds[:-1], bounds[1:]):
+            lg, ws = sx.verify_tree_range(mw, pkd, pvd, P, to_dev(tok[:hi]), to_dev(par[:hi]), lo, tree_k, tree_v)
+            torch.cuda.synchronize()
+            assert sx.check_status(ws) == 0
+            rows.append(lg.cpu().double().numpy())
+        got = np.concatenate(rows, axis=0)
+        assert got.shape == ref["logits"].shape
+        assert np.abs(got - ref["logits"]).max() <= 1e-4
+        np.testing.assert_allclose(tree_k[:, :T].cpu().double().numpy(), ref["tree_k"], atol=1e-4)
+        np.testing.assert_allclose(tree_v[:, :T].cpu().double().numpy(), ref["tree_v"], atol=1e-4)
+
+
+def test_bf16_tree_verified_in_batches_matches_one_pass(sx):
+    """Same on the MFMA path (4 narrow bf16 layers, GQA): batches of nodes against the one-pass result.  The
+    batches change which keys share an attention tile, hence the order of fp32 sums: bf16 roundings may flip, so
+    the bar is the bf16 one (2e-2 on the logits) with nearly all of them agreeing far more closely."""
+    cfg = wl.ModelCfg(4, 1024, 8, 2, 128, 2752, 4000, dtype="bf16")
+    w = wl.gen_weights(cfg, seed=41)
+    P = 70
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=42)
+    tok, par, _ = wl.gen_best_first_tree(150, 6, cfg.vocab, seed=43)
+    T = len(tok)
+    mw = sx.ModelWeights(cfg, weights_to(w, dev()))
+    pkd, pvd = pk.to(dev()), pv.to(dev())
+    one, ws = sx.verify_tree(mw, pkd, pvd, to_dev(tok), to_dev(par))
+    torch.cuda.synchronize()
+    one = one.cpu().double().numpy()
+    tree_k = torch.zeros((cfg.n_layers, T, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device=dev())
+    tree_v = torch.zeros_like(tree_k)
+    rows = []
+    bounds = [0, 1, 17, 64, 65, 130, T]
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        lg, ws = sx.verify_tree_range(mw, pkd, pvd, P, to_dev(tok[:hi]), to_dev(par[:hi]), lo, tree_k, tree_v)
+        torch.cuda.synchronize()
+        assert sx.check_status(ws) == 0
+        rows.append(lg.cpu().double().numpy())
+    got = np.concatenate(rows, axis=0)
+    diff = np.abs(got - one)
+    assert diff.max() <= TOL_BF16 and np.quantile(diff, 0.99) <= 5e-3, (diff.max(), np.quantile(diff, 0.99))
+
+
 def test_commit_kv_bf16_gathers_path_rows(sx):
     """sx_commit_kv alone, bf16 rows of 2 KB, n read from the device: byte-exact gather, rows past n untouched."""
     cfg = wl.ModelCfg(3, 1024, 8, 8, 128, 2752, 4000, dtype="bf16")
