@@ -15,5 +15,6 @@ from .model import (  # noqa: F401
     round_bf16,
 )
 from .generate import specexec_generate  # noqa: F401
+from .draft import create_draft_tree  # noqa: F401
 from .sampling import uniform01, sample_token, accept_walk, sequential_sample  # noqa: F401
 from .expand import log_softmax, row_topk, expand_topk  # noqa: F401
