@@ -209,6 +209,35 @@ int sx_specexec_round(const sx_weights *w, void *cache_k, void *cache_v, int32_t
                       void *tree_v, int32_t *path_out, int32_t *tokens_out, int32_t *n_out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * sx_draft_tree -- Alg. 2, PARALLEL SSSP FOR DRAFTING: createDraftTree(x, theta_draft, K, D, B).
+ *
+ * Builds the tree of likely continuations of the root token with the draft model `w`, entirely on
+ * the stream (no host synchronisation between iterations).  Each of the D iterations pops the up
+ * to B best candidates from the priority queue (ordered by cumulative log-probability, ties to the
+ * candidate that entered first; the queue is first cut to its K best), makes those above the
+ * threshold tree nodes (threshold: the K-th best score in the tree once it holds K nodes), runs the
+ * draft model over them (they attend to the prefix and to their tree ancestors), keeps per node its k
+ * most probable next tokens and of those the min(K, B k) best by cumulative log-probability, and
+ * inserts them into the queue.  Finally the tree is cut to its K best nodes.
+ *
+ *   prefix_k, prefix_v  the DRAFT model's cache, device [L][capacity][Hkv][Dh], rows [0, P) valid
+ *   root_token          device int32 [1]: the last accepted token (e.g. tokens_out[n-1] of the walk)
+ *   tree_tokens_out, parent_out   device int32 [K]; cum_logp_out device float [K]; n_out device
+ *                       int32 [1] (1 <= n <= K).  Nodes in order of insertion (parents before
+ *                       children, node 0 = root with parent -1): the input sx_verify_tree expects.
+ * Supported: D * B <= 16384, k <= 256 (k is clamped to the vocabulary), min(K, B k) <= 8192,
+ * K + min(K, B k) <= 16384, and the model shapes of sx_verify_tree with T = D * B.
+ * workspace: sx_draft_tree_workspace bytes, 256-byte aligned; sx_check_status on it reports the
+ * status of the forward passes.
+ * ---------------------------------------------------------------------------------------- */
+size_t sx_draft_tree_workspace(const sx_model_cfg *cfg, int32_t P, int32_t K, int32_t D, int32_t B,
+                               int32_t k);
+int sx_draft_tree(const sx_weights *w, const void *prefix_k, const void *prefix_v, int32_t capacity,
+                  int32_t P, const int32_t *root_token, int32_t K, int32_t D, int32_t B, int32_t k,
+                  int32_t *tree_tokens_out, int32_t *parent_out, float *cum_logp_out, int32_t *n_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* Reads the device-side status word of a workspace used by one of the calls above.
  * Synchronises `stream`.  Returns SX_OK, SX_ERR_TREE, or SX_ERR_HIP. */
 int sx_check_status(const void *workspace, void *stream);

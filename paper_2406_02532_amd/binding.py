@@ -9,7 +9,7 @@ import torch
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
 EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
-           "sx_specexec_round_workspace", "sx_specexec_round", "sx_accept_walk_workspace", "sx_accept_walk",
+           "sx_specexec_round_workspace", "sx_specexec_round", "sx_draft_tree_workspace", "sx_draft_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
            "sx_profile_enable", "sx_profile_disable", "sx_profile_read"]
@@ -62,6 +62,10 @@ def _load():
     L.sx_specexec_round.restype = C.c_int
     L.sx_specexec_round.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, vp, i32, f32, f32, u64, vp, vp, vp, vp, vp,
                                     vp, vp, sz, vp]
+    L.sx_draft_tree_workspace.restype = sz
+    L.sx_draft_tree_workspace.argtypes = [C.POINTER(_Cfg), i32, i32, i32, i32, i32]
+    L.sx_draft_tree.restype = C.c_int
+    L.sx_draft_tree.argtypes = [C.POINTER(_Weights), vp, vp, i32, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     L.sx_accept_walk_workspace.argtypes = [i32, i32]
     L.sx_accept_walk.restype = C.c_int
     L.sx_accept_walk.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
@@ -229,6 +233,27 @@ def specexec_round(weights: ModelWeights, cache_k, cache_v, P: int, tree_tokens,
                                buf.workspace.numel(), _stream(stream))
     _check(rc, "sx_specexec_round")
     return buf
+
+
+def draft_tree(weights: ModelWeights, prefix_k, prefix_v, P: int, root_token, K: int, D: int, B: int, k: int,
+               workspace=None, stream=None):
+    """sx_draft_tree: (tokens [K], parent [K], cum_logp [K], n [1], workspace) -- device tensors, nothing synchronised."""
+    cfg, dev = weights.cfg, weights.device
+    c = _make_cfg(cfg)
+    capacity = 0 if prefix_k is None else int(prefix_k.shape[1])
+    toks = torch.zeros(K, dtype=torch.int32, device=dev)
+    par = torch.zeros(K, dtype=torch.int32, device=dev)
+    cum = torch.zeros(K, dtype=torch.float32, device=dev)
+    n = torch.zeros(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        nbytes = lib.sx_draft_tree_workspace(C.byref(c), P, K, D, B, k)
+        if nbytes == 0:
+            raise SxError(-2, "sx_draft_tree_workspace")
+        workspace = _workspace(nbytes, dev)
+    _check(lib.sx_draft_tree(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), capacity, P, _ptr(root_token), K, D, B, k,
+                             _ptr(toks), _ptr(par), _ptr(cum), _ptr(n), _ptr(workspace), workspace.numel(),
+                             _stream(stream)), "sx_draft_tree")
+    return toks, par, cum, n, workspace
 
 
 def accept_walk(logits, tree_tokens, parent_idx, temperature: float, top_p: float, seed: int, pos0: int,
