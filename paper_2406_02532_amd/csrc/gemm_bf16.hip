@@ -299,8 +299,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 
   // The loop body is branch-free: past the end of K it copies the last slab again, into a stage nobody
   // reads any more, and reads fragments nobody uses.
-  const int NB = a.K / BK / ksplit;          // slabs of this workgroup
-  const int first = kpart * NB, last = first + NB - 1;
+  const int nb_all = a.K / BK;
+  const int first = kpart * nb_all / ksplit;                      // slabs of this workgroup: [first, first + NB)
+  const int NB = (kpart + 1) * nb_all / ksplit - first, last = first + NB - 1;
   SX_COPY(stA, first)
   SX_COPY(stB, min(first + 1, last))
   SX_WAIT_BARRIER(kWaitVm16)
@@ -493,8 +494,11 @@ int compute_units() {
   return n;
 }
 
-// Decides whether the last tiles get a K split: only when they would fill at most half of the chip for
-// a whole round, the caller gave memory for the partial sums, and every part keeps at least 8 slabs.
+// Decides whether the last tiles get a K split: only when there are more tiles than compute units with a
+// remainder that would fill at most half of the chip for a whole round, and the caller gave memory for the
+// partial sums; at most 4 ways, parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
+// small M, the draft model's batches -- was measured too: the partial sums, 256 KB per part, then outweigh
+// the weights being streamed, and the launch gets slower; such shapes want narrower tiles, not a K split.)
 void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   a.split = 1;
   a.part = nullptr;
@@ -506,9 +510,9 @@ void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   if (rest == 0 || 2 * rest > cus) return;
   int split = cus / rest;
   if (split > 4) split = 4;
-  while (split > 1 && (nb % split != 0 || nb / split < 8)) --split;
-  if (split < 2) return;
-  if (split_ws_bytes < sx_gemm_split_workspace(a.M, a.N)) return;
+  while (split > 1 && nb / split < 8) --split;
+  if (split < 2 || rest > 256) return;
+  if (split_ws_bytes < 1024 + (size_t)rest * split * BM * BN * sizeof(float)) return;
   a.split = split;
   a.full_tiles = tiles - rest;
   a.tail_items = rest * split;
@@ -532,7 +536,7 @@ int launch(const GemmArgs& a, hipStream_t st) {
 }  // namespace
 
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
-                        void* Y, int M, int K, int mode, hipStream_t st) {
+                        void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || n0 < 1) return SX_ERR_SHAPE;
   // a 16-row copy group must not straddle two stacked weight matrices
   if (mode != SX_GEMM_SWIGLU && ((n1 > 0 && n0 % 16 != 0) || (n2 > 0 && n1 % 16 != 0))) return SX_ERR_SHAPE;
@@ -557,7 +561,7 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
     a.tilesN = (a.N + BN - 1) / BN;
   }
   a.chunk = (a.tilesM * a.tilesN + 7) / 8;
-  plan_split(a, nullptr, 0);
+  plan_split(a, split_ws, split_ws_bytes);
   switch (mode) {
     case SX_GEMM_STORE: return launch<SX_GEMM_STORE>(a, st);
     case SX_GEMM_RESIDUAL: return launch<SX_GEMM_RESIDUAL>(a, st);
@@ -566,13 +570,8 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
   return SX_ERR_SHAPE;
 }
 
-// 1 KB of counters (at most 128 tail tiles, zero before the first launch) and up to one partial tile per
-// compute unit (fewer than 256 of them are counted on).
-size_t sx_gemm_split_workspace(int M, int N) {
-  const size_t tiles = (size_t)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const size_t parts = tiles < 512 ? tiles : 512;
-  return 1024 + parts * (size_t)BM * BN * sizeof(float);
-}
+// 1 KB of counters (at most 256 split tiles, zero before the first launch) and one partial tile per compute unit
+size_t sx_gemm_split_workspace() { return 1024 + (size_t)compute_units() * BM * BN * sizeof(float); }
 
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
                                  const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
@@ -606,6 +605,7 @@ extern "C" int sx_gemm_bf16(const void* X, const void* W, const void* W2, void* 
                             int32_t mode, void* stream) {
   if (!X || !W || !Y || (mode == SX_GEMM_SWIGLU && !W2)) return SX_ERR_NULL;
   if (mode < 0 || mode > 2 || N < 1) return SX_ERR_SHAPE;
-  if (mode == SX_GEMM_SWIGLU) return sx_launch_gemm_bf16(X, W, W2, nullptr, N, N, 0, Y, M, K, mode, (hipStream_t)stream);
-  return sx_launch_gemm_bf16(X, W, nullptr, nullptr, N, 0, 0, Y, M, K, mode, (hipStream_t)stream);
+  if (mode == SX_GEMM_SWIGLU)
+    return sx_launch_gemm_bf16(X, W, W2, nullptr, N, N, 0, Y, M, K, mode, nullptr, 0, (hipStream_t)stream);
+  return sx_launch_gemm_bf16(X, W, nullptr, nullptr, N, 0, 0, Y, M, K, mode, nullptr, 0, (hipStream_t)stream);
 }

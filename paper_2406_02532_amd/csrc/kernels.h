@@ -40,13 +40,15 @@ int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_
 enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2, SX_GEMM_QKV_ROPE = 3 };
 // Y = X [W0;W1;W2]^T with n0/n1/n2 rows per segment (modes 0/1, Y fp32 [M][n0+n1+n2]), or
 // Y bf16 [M][n0] = silu(X W0^T) * (X W1^T) (mode 2, n1 == n0, n2 == 0).
+// split_ws: see sx_gemm_split_workspace (may be null).
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
-                        void* Y, int M, int K, int mode, hipStream_t st);
+                        void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st);
 // q, k, v (bf16 [M][hq][128], [M][hkv][128], [M][hkv][128]) = rotary(X [Wq;Wk;Wv]^T): the QKV projection with
 // the split into heads and the rotation by rope_cs[M][64] = (cos, sin) done in the GEMM's epilogue (v unrotated).
-// split_ws (may be null: then no split): sx_gemm_split_workspace(M, N) bytes whose first 1 KB is zero before the first
-// launch (the kernel leaves it zero); lets the last tiles of a launch that fills the chip unevenly be cut along K.
-size_t sx_gemm_split_workspace(int M, int N);
+// split_ws (may be null: then no split): sx_gemm_split_workspace() bytes whose first 1 KB is zero before the first
+// launch (the kernel leaves it zero); lets the tiles of a launch that fills the chip unevenly, or hardly at all, be
+// cut along K and summed by the last workgroup to arrive.
+size_t sx_gemm_split_workspace();
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
                                  const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
                                  size_t split_ws_bytes, hipStream_t st);

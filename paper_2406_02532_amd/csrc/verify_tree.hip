@@ -43,10 +43,10 @@ Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
   L.rope_cs = cv.take<float2>((size_t)T * (c.head_dim / 2));
   L.h = cv.take<float>((size_t)T * c.d_model);
   L.x = cv.take<char>((size_t)T * c.d_model * es);
-  // fp32 QKV for the unfused paths; the fused bf16 path (head_dim 128) keeps its K-split partial sums here
+  // fp32 QKV for the unfused paths, and the K-split partial sums of the bf16 GEMMs (never both at once)
   {
     const size_t plain = (size_t)T * (Nq + 2 * Nkv) * sizeof(float);
-    const size_t split = sx_gemm_split_workspace(T, (int)(Nq + 2 * Nkv));
+    const size_t split = sx_gemm_split_workspace();
     L.qkv_bytes = plain > split ? plain : split;
     L.qkv = reinterpret_cast<float*>(cv.take<char>(L.qkv_bytes));
   }
@@ -161,7 +161,10 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
                                              L.rowmask, st));
   SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s + first, n, d, L.h, st));
   const float2* rope_cs = L.rope_cs + (size_t)first * (Dh / 2);  // rows of this call's nodes
-  if (bf && Dh == 128) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(L.qkv), 256, st));  // K-split counters
+  // K-split partial sums share the fp32 QKV buffer, which only the unfused bf16 QKV path (head_dim != 128) also uses
+  void* split_ws = (bf && Dh == 128) ? static_cast<void*>(L.qkv) : nullptr;
+  const size_t split_bytes = split_ws ? L.qkv_bytes : 0;
+  if (split_ws) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(L.qkv), 256, st));  // K-split counters
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
@@ -182,7 +185,7 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
                                             L.qkv_bytes, st));
     } else if (bf) {
       SX_TIMED(SX_K_GEMM_QKV,
-               sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, n, d, SX_GEMM_STORE, st));
+               sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, n, d, SX_GEMM_STORE, split_ws, split_bytes, st));
     } else {
       const int ld = Nq + 2 * Nkv;
       const float* x = static_cast<const float*>(L.x);
@@ -196,12 +199,12 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
       SX_TIMED(SX_K_ATTN, sx_launch_tree_attn_bf16(L.q, tkb, tvb, pk, pv, L.klist, L.kcnt, L.rowmask, T, n, P, Hq, Hkv,
                                                    L.o, st));
       SX_TIMED(SX_K_GEMM_O,
-               sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, n, Nq, SX_GEMM_RESIDUAL, st));
+               sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, n, Nq, SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
       SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
       SX_TIMED(SX_K_GEMM_GATEUP,
-               sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, n, d, SX_GEMM_SWIGLU, st));
+               sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, n, d, SX_GEMM_SWIGLU, split_ws, split_bytes, st));
       SX_TIMED(SX_K_GEMM_DOWN,
-               sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, n, F, SX_GEMM_RESIDUAL, st));
+               sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, n, F, SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
     } else {
       SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tkb, (const float*)tvb, (const float*)pk,
                                      (const float*)pv, L.par_s, L.depth, T, first, P, Hq, Hkv, Dh, (float*)L.o, st));
@@ -216,7 +219,7 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
   SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, w->final_norm, c.dtype, n, d, c.rms_eps, L.x, st));
   if (bf)
     SX_TIMED(SX_K_GEMM_LMHEAD,
-             sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, n, d, SX_GEMM_STORE, st));
+             sx_launch_gemm_bf16(L.x, w->lm_head, nullptr, nullptr, V, 0, 0, logits_out, n, d, SX_GEMM_STORE, split_ws, split_bytes, st));
   else
     SX_TRY(sx_launch_gemm_f32((const float*)L.x, (const float*)w->lm_head, logits_out, n, V, d, V, false, st));
   return SX_OK;
@@ -346,7 +349,7 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
 static size_t qkv_rope_table_bytes(int32_t T) { return (((size_t)T * 64 * sizeof(float2)) + 255) & ~(size_t)255; }
 extern "C" size_t sx_qkv_rope_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads) {
   if (T < 1 || n_q_heads < 1 || n_kv_heads < 1) return 0;
-  return qkv_rope_table_bytes(T) + sx_gemm_split_workspace(T, (n_q_heads + 2 * n_kv_heads) * 128);
+  return qkv_rope_table_bytes(T) + sx_gemm_split_workspace();
 }
 
 extern "C" int sx_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int32_t T, int32_t d_model,
