@@ -46,7 +46,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C5"])
+    ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C5", "draft7b"],
+                    help="C5 (default): the headline step.  draft7b: a side measurement, sx_draft_tree with a 32-layer "
+                         "Llama-2-7B-shaped draft model (not the headline metric)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (development only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -66,6 +68,8 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "draft7b":
+        return bench_draft(args, sx, wl, torch, np, dev)
     c = wl.CONFIGS[args.workload]
     cfg = c["cfg"] if not args.layers else c["cfg"].with_layers(args.layers)
     P, T, k_tree = c["P"], c["T"], c["k"]
@@ -198,6 +202,54 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p)
     print(json.dumps(out), flush=True)
+
+
+def bench_draft(args, sx, wl, torch, np, dev):
+    """Side measurement: createDraftTree (Alg. 2) on the device with a Llama-2-7B-shaped 32-layer bf16 draft model,
+    2048 cached prefix tokens, budget K=2048, D=24 iterations of B=128 nodes, k=32 children per node."""
+    cfg = wl.CONFIGS["C2"]["cfg"].with_layers(args.layers or 32)
+    K, D, B, k, P = 2048, 24, 128, 32, 2048
+    w = wl.gen_weights(cfg, seed=5, device=dev)
+    w["lm_head"] = (w["lm_head"].float() * 8).to(torch.bfloat16)      # sharper next-token distributions than N(0, 0.02)
+    mw = sx.ModelWeights(cfg, w)
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=6, device=dev)
+    root = torch.tensor([17], dtype=torch.int32, device=dev)
+    toks, par, cum, n, ws = sx.draft_tree(mw, pk, pv, P, root, K, D, B, k)
+    for _ in range(max(args.warmup - 1, 0)):
+        sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws)
+    torch.cuda.synchronize()
+    assert sx.check_status(ws) == 0
+    launches = D * (12 * cfg.n_layers + 24) + 8
+    sx.profile_enable(launches * args.steps + 64)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    sx.profile_disable()
+    agg = {}
+    for name, t in sx.profile_read(launches * args.steps + 64):
+        a = agg.setdefault(name, [0, 0.0])
+        a[0] += 1
+        a[1] += t
+    nn = int(n.item())
+    par_h = par[:nn].cpu().numpy()
+    depth = np.zeros(nn, dtype=np.int64)
+    for i in range(1, nn):
+        depth[i] = depth[par_h[i]] + 1
+    nparam = sum(v.numel() for lw in w["layers"] for v in lw.values()) + w["embed"].numel() + w["lm_head"].numel()
+    print(json.dumps(dict(
+        metric="draft tree construction time (side measurement, not the headline)", value=round(ms, 3), unit="ms",
+        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms, 3), higher_is_better=False, scaling="weak",
+        vs_baseline=None, dtype="bf16", data="synthetic",
+        config=dict(workload="draft7b: %d-layer Llama-2-7B-shaped draft (d=%d, %d heads x %d, FFN %d, vocab %d), prefix %d, "
+                             "sx_draft_tree K=%d D=%d B=%d k=%d" % (cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.head_dim,
+                                                                     cfg.d_ffn, cfg.vocab, P, K, D, B, k),
+                    parameters_GB=round(nparam * 2 / 1e9, 1)),
+        ms_per_iteration=round(ms / D, 3), tree=dict(nodes=nn, max_depth=int(depth.max())),
+        weight_streaming_floor_ms_per_iteration=round(nparam * 2 / 5.0e12 * 1e3, 3),
+        kernels={k_: dict(launches_per_tree=v[0] / args.steps, ms_per_tree=round(v[1] / args.steps, 3))
+                 for k_, v in sorted(agg.items(), key=lambda kv: -kv[1][1])})), flush=True)
 
 
 def cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p):

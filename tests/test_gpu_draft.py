@@ -83,3 +83,84 @@ def test_draft_tree_rejects_unsupported_shapes(sx, draft):
         sx.draft_tree(mw, None, None, 0, root, 10, 20000, 1, 4)          # D * B over the limit
     with pytest.raises(sx.SxError):
         sx.draft_tree(mw, None, None, 0, root, 0, 4, 4, 4)               # K < 1
+
+
+@pytest.mark.parametrize("draft_kind", ["unrelated", "self"])
+def test_speculative_generation_end_to_end_equals_sequential_sampling(sx, draft_kind):
+    """The whole of Alg. 1 with Alg. 2 inside, every step on the device: each round the draft model builds a tree
+    (sx_draft_tree), the target verifies it, walks it and commits the accepted nodes (sx_specexec_round), and the
+    draft model's own cache is brought up to date.  Sect. 4.1: the emitted tokens are exactly what token-by-token
+    sampling from the TARGET model gives with the same seed, whatever the draft model proposes."""
+    tcfg = wl.ModelCfg(2, 256, 4, 4, 64, 688, 1024, dtype="fp32")
+    dcfg = wl.ModelCfg(1, 128, 4, 2, 32, 256, 1024, dtype="fp32")
+    tw = wl.gen_weights(tcfg, seed=71)
+    tw = dict(tw, lm_head=tw["lm_head"] * 20.0)
+    # "unrelated": another random model, whose guesses the target almost never accepts (one token per round);
+    # "self": the target drafts for itself, so most rounds accept several tokens
+    if draft_kind == "self":
+        dcfg, dw = tcfg, tw
+    else:
+        dw = wl.gen_weights(dcfg, seed=72)
+        dw = dict(dw, lm_head=dw["lm_head"] * 10.0)
+    twn, dwn = weights_np(tw), weights_np(dw)
+    prompt = [int(t) for t in wl.gen_tokens(12, tcfg.vocab, seed=73)]
+    P0 = len(prompt) - 1
+    _, tpk, tpv = oracle.path_forward(tcfg, twn, None, None, prompt[:-1], return_kv=True)
+    _, dpk, dpv = oracle.path_forward(dcfg, dwn, None, None, prompt[:-1], return_kv=True)
+    tmw, dmw = sx.ModelWeights(tcfg, weights_to(tw, dev())), sx.ModelWeights(dcfg, weights_to(dw, dev()))
+    rounds, K, D, B, k = 4, 24, 5, 8, 4
+    cap = P0 + rounds * K
+    checked, accepted = 0, 0
+    for s in range(40):
+        if checked >= 3:
+            break
+        truth = oracle.sequential_sample(tcfg, twn, tpk, tpv, prompt[-1], rounds * 4 + 2, 0.6, 0.9, seed=s, pos0=P0)
+        seq, safe = [prompt[-1]], True
+        for x in truth:                                                # every decision safely away from a tie
+            lg = oracle.path_forward(tcfg, twn, tpk, tpv, seq)
+            _, m = oracle.sample_token(lg, 0.6, 0.9, oracle.uniform01(s, P0 + len(seq)))
+            safe &= min(m["m_p"], m["m_u"]) > 1e-3
+            seq.append(x)
+        if not safe:
+            continue
+
+        def cache(cfg, pk, pv):
+            ck = torch.zeros((cfg.n_layers, cap, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device=dev())
+            cv = torch.zeros_like(ck)
+            ck[:, :P0] = to_dev(torch.as_tensor(pk), torch.float32)
+            cv[:, :P0] = to_dev(torch.as_tensor(pv), torch.float32)
+            return ck, cv
+        tck, tcv = cache(tcfg, tpk, tpv)
+        dck, dcv = cache(dcfg, dpk, dpv)
+        buf = sx.RoundBuffers(tmw, cap, K)
+        P, root, emitted = P0, torch.tensor([prompt[-1]], dtype=torch.int32, device=dev()), []
+        for rd in range(rounds):
+            toks, par, cum, n, ws = sx.draft_tree(dmw, dck, dcv, P, root, K, D, B, k)
+            torch.cuda.synchronize()
+            assert sx.check_status(ws) == 0
+            nt = int(n.item())
+            tree_t, tree_p = toks[:nt].contiguous(), par[:nt].contiguous()
+            sx.specexec_round(tmw, tck, tcv, P, tree_t, tree_p, 0.6, 0.9, s, buf)
+            torch.cuda.synchronize()
+            assert sx.check_status(buf.workspace) == 0
+            na = int(buf.n.item())
+            out = buf.tokens[:na].cpu().tolist()
+            # the draft model's cache takes the same accepted tokens: a chain forward, then the same commit
+            chain = torch.tensor([int(root.item())] + out[:-1], dtype=torch.int32, device=dev())
+            cpar = torch.arange(-1, na - 1, dtype=torch.int32, device=dev())
+            dk = torch.zeros((dcfg.n_layers, na, dcfg.n_kv_heads, dcfg.head_dim), dtype=torch.float32, device=dev())
+            dv = torch.zeros_like(dk)
+            sx.verify_tree(dmw, dck, dcv, chain, cpar, tree_k_out=dk, tree_v_out=dv, P=P)
+            sx.commit_kv(dcfg, dck, dcv, P, dk, dv, torch.arange(na, dtype=torch.int32, device=dev()),
+                         torch.tensor([na], dtype=torch.int32, device=dev()))
+            emitted += out
+            P += na
+            root = torch.tensor([out[-1]], dtype=torch.int32, device=dev())
+        if len(emitted) > len(truth):        # more accepted than the margin check covered: compare what it covers
+            emitted = emitted[:len(truth)]
+        assert emitted == truth[:len(emitted)] and len(emitted) >= rounds
+        accepted += len(emitted) - rounds
+        checked += 1
+    assert checked >= 3
+    if draft_kind == "self":
+        assert accepted >= 3                 # drafting with the target itself must get draft tokens accepted
