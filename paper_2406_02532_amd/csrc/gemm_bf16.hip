@@ -538,6 +538,8 @@ int launch(const GemmArgs& a, hipStream_t st) {
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                         void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || n0 < 1) return SX_ERR_SHAPE;
+  if (M <= 128)  // weight-streaming regime: narrow tiles
+    return sx_launch_gemm_skinny_bf16(X, W0, W1, W2, n0, n1, n2, Y, M, K, mode, split_ws, split_ws_bytes, st);
   // a 16-row copy group must not straddle two stacked weight matrices
   if (mode != SX_GEMM_SWIGLU && ((n1 > 0 && n0 % 16 != 0) || (n2 > 0 && n1 % 16 != 0))) return SX_ERR_SHAPE;
   GemmArgs a;

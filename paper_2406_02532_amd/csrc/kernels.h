@@ -40,6 +40,9 @@ int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_
 enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2, SX_GEMM_QKV_ROPE = 3 };
 // Y = X [W0;W1;W2]^T with n0/n1/n2 rows per segment (modes 0/1, Y fp32 [M][n0+n1+n2]), or
 // Y bf16 [M][n0] = silu(X W0^T) * (X W1^T) (mode 2, n1 == n0, n2 == 0).
+// Same contract for M <= 128 (narrow tiles; modes store, residual, SwiGLU); sx_launch_gemm_bf16 forwards to it.
+int sx_launch_gemm_skinny_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
+                               void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st);
 // split_ws: see sx_gemm_split_workspace (may be null).
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                         void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st);
@@ -59,7 +62,19 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
                              const unsigned long long* rowmask, int T, int Tq, int P, int Hq, int Hkv, void* out,
                              hipStream_t st);
-static inline int sx_attn_nodes_per_tile(int Hq, int Hkv) { return 128 / (Hq / Hkv); }
+// Query nodes per attention workgroup: 128 rows / G, fewer (down to one wave's 32 rows) when there are so few
+// query nodes that the grid would leave most of the chip idle -- the draft model's small batches.  The
+// workspace is sized for the smallest value.
+static inline int sx_attn_min_nodes_per_tile(int Hq, int Hkv) {
+  const int G = Hq / Hkv;
+  return G >= 32 ? 1 : 32 / G;
+}
+static inline int sx_attn_nodes_per_tile(int Hq, int Hkv, int Tq) {
+  int npt = 128 / (Hq / Hkv);
+  const int lo = sx_attn_min_nodes_per_tile(Hq, Hkv);
+  while (npt > lo && ((Tq + npt - 1) / npt) * Hkv < 256) npt /= 2;
+  return npt;
+}
 
 // ---- optional event timing around single launches (prof.hip) -----------------------------------------
 enum {

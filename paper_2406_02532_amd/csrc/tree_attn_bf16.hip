@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   const int r = wave * 32 + l32;
   const int node = n0 + r / a.G;
   const int head = kvh * a.G + r % a.G;
-  const bool row_ok = node < a.Tq;
+  const bool row_ok = node < a.Tq && r / a.G < a.npt;  // tiles of fewer than 128 rows leave waves without rows
   bf16x8 qf[8];
   {
     const unsigned short* qp = a.q + ((size_t)(row_ok ? node : 0) * a.Hq + head) * DH + lh * 8;
@@ -308,7 +308,7 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
   a.Hq = Hq;
   a.Hkv = Hkv;
   a.G = G;
-  a.npt = QROWS / G;
+  a.npt = sx_attn_nodes_per_tile(Hq, Hkv, Tq);  // the same value the tile lists were built with
   a.W64 = (T + 63) / 64;
   dim3 grid((Tq + a.npt - 1) / a.npt, Hkv);
   tree_attn_bf16_kernel<<<grid, kThreads, 0, st>>>(a);

@@ -26,7 +26,8 @@ struct Layout {
   unsigned long long* rowmask;
   float *h, *qkv, *gate, *up;
   void *x, *q, *o, *act, *tk, *tv;
-  size_t qkv_bytes;
+  void* split_ws;
+  size_t split_bytes;
   size_t bytes;
 };
 
@@ -43,20 +44,16 @@ Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
   L.rope_cs = cv.take<float2>((size_t)T * (c.head_dim / 2));
   L.h = cv.take<float>((size_t)T * c.d_model);
   L.x = cv.take<char>((size_t)T * c.d_model * es);
-  // fp32 QKV for the unfused paths, and the K-split partial sums of the bf16 GEMMs (never both at once)
-  {
-    const size_t plain = (size_t)T * (Nq + 2 * Nkv) * sizeof(float);
-    const size_t split = sx_gemm_split_workspace();
-    L.qkv_bytes = plain > split ? plain : split;
-    L.qkv = reinterpret_cast<float*>(cv.take<char>(L.qkv_bytes));
-  }
+  L.qkv = cv.take<float>((size_t)T * (Nq + 2 * Nkv));  // fp32 QKV of the paths that rotate in a kernel of their own
+  L.split_bytes = c.dtype == SX_BF16 ? sx_gemm_split_workspace() : 0;  // K-split counters and partial sums of the GEMMs
+  L.split_ws = L.split_bytes ? cv.take<char>(L.split_bytes) : nullptr;
   L.q = cv.take<char>((size_t)T * Nq * es);
   L.tk = cv.take<char>((size_t)T * Nkv * es);
   L.tv = cv.take<char>((size_t)T * Nkv * es);
   L.o = cv.take<char>((size_t)T * Nq * es);
   L.act = cv.take<char>((size_t)T * c.d_ffn * es);
   if (c.dtype == SX_BF16) {
-    const int npt = sx_attn_nodes_per_tile(c.n_q_heads, c.n_kv_heads);
+    const int npt = sx_attn_min_nodes_per_tile(c.n_q_heads, c.n_kv_heads);
     const size_t tiles = (T + npt - 1) / npt;
     L.klist = cv.take<int32_t>(tiles * (size_t)T);
     L.kcnt = cv.take<int32_t>(tiles);
@@ -157,14 +154,13 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
   SX_TIMED(SX_K_PREP, sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth,
                                           L.rope_cs, status, st));
   if (bf)
-    SX_TIMED(SX_K_PREP, sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv), first, L.klist, L.kcnt,
+    SX_TIMED(SX_K_PREP, sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv, n), first, L.klist, L.kcnt,
                                              L.rowmask, st));
   SX_TIMED(SX_K_EMBED, sx_launch_embed(w->embed, c.dtype, L.tok_s + first, n, d, L.h, st));
   const float2* rope_cs = L.rope_cs + (size_t)first * (Dh / 2);  // rows of this call's nodes
-  // K-split partial sums share the fp32 QKV buffer, which only the unfused bf16 QKV path (head_dim != 128) also uses
-  void* split_ws = (bf && Dh == 128) ? static_cast<void*>(L.qkv) : nullptr;
-  const size_t split_bytes = split_ws ? L.qkv_bytes : 0;
-  if (split_ws) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(L.qkv), 256, st));  // K-split counters
+  void* split_ws = L.split_ws;
+  const size_t split_bytes = L.split_bytes;
+  if (split_ws) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(split_ws), 256, st));  // K-split counters
 
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
@@ -178,11 +174,13 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
     const void* pv = P > 0 ? static_cast<const char*>(prefix_v) + pre_layer : nullptr;
 
     SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.attn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
-    const bool fused_rope = bf && Dh == 128;  // the GEMM's epilogue rotates and splits into heads
+    // the wide GEMM's epilogue rotates and splits into heads; small batches (the draft model's) take the narrow
+    // GEMM, whose 64-column tiles do not hold a whole head, and rotate in a kernel of their own
+    const bool fused_rope = bf && Dh == 128 && n > 128;
     if (fused_rope) {
       SX_TIMED(SX_K_GEMM_QKV,
-               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, rope_cs, L.q, tk, tv, n, d, L.qkv,
-                                            L.qkv_bytes, st));
+               sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, rope_cs, L.q, tk, tv, n, d, split_ws,
+                                            split_bytes, st));
     } else if (bf) {
       SX_TIMED(SX_K_GEMM_QKV,
                sx_launch_gemm_bf16(L.x, lw.wq, lw.wk, lw.wv, Nq, Nkv, Nkv, L.qkv, n, d, SX_GEMM_STORE, split_ws, split_bytes, st));
@@ -323,7 +321,7 @@ bool attn_shape_ok(int T, int Hq, int Hkv) {
 
 extern "C" size_t sx_tree_attention_workspace(int32_t T, int32_t n_q_heads, int32_t n_kv_heads) {
   if (!attn_shape_ok(T, n_q_heads, n_kv_heads)) return 0;
-  return carve_attn(T, sx_attn_nodes_per_tile(n_q_heads, n_kv_heads), nullptr).bytes;
+  return carve_attn(T, sx_attn_min_nodes_per_tile(n_q_heads, n_kv_heads), nullptr).bytes;
 }
 
 extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
@@ -334,8 +332,8 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
   if (P > 0 && (!k_prefix || !v_prefix)) return SX_ERR_NULL;
   if (P < 0 || !attn_shape_ok(T, n_q_heads, n_kv_heads)) return SX_ERR_SHAPE;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
-  const int npt = sx_attn_nodes_per_tile(n_q_heads, n_kv_heads);
-  const AttnLayout L = carve_attn(T, npt, workspace);
+  const int npt = sx_attn_nodes_per_tile(n_q_heads, n_kv_heads, T);
+  const AttnLayout L = carve_attn(T, sx_attn_min_nodes_per_tile(n_q_heads, n_kv_heads), workspace);
   if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   SX_TRY(sx_launch_tree_prep(nullptr, parent_idx, T, 1, P, 128, 10000.f, L.tok_s, L.par_s, L.depth, L.cs,
