@@ -300,7 +300,8 @@ def test_commit_kv_bf16_gathers_path_rows(sx):
 # bf16 building blocks
 # ------------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 256), (300, 200, 128), (1, 1000, 192), (520, 768, 4096)])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 256), (300, 200, 128), (1, 1000, 192), (520, 768, 4096),
+                                   (128, 4096, 11008), (33, 72, 64), (100, 130, 320)])
 def test_gemm_bf16_store_and_residual(sx, M, N, K):
     X = wl.hash_normal(1, (M, K), dtype=torch.bfloat16)
     W = wl.hash_normal(2, (N, K), std=0.05, dtype=torch.bfloat16)
@@ -315,7 +316,21 @@ def test_gemm_bf16_store_and_residual(sx, M, N, K):
     assert np.abs(Y.cpu().double().numpy() - 2 * ref).max() <= 2 * tol
 
 
-@pytest.mark.parametrize("M,F,K", [(256, 128, 64), (300, 200, 256), (100, 11008, 128)])
+@pytest.mark.parametrize("M", [64, 128, 129, 300])
+def test_gemm_bf16_llama3_vocabulary_head(sx, M):
+    """lm_head at a 128256-token vocabulary (Llama-3 shape), on both sides of the 128-row switch between the
+    narrow-tile and the wide-tile kernel; K kept small so that the fp64 product stays cheap."""
+    N, K = 128256, 256
+    X = wl.hash_normal(21, (M, K), dtype=torch.bfloat16)
+    W = wl.hash_normal(22, (N, K), std=0.05, dtype=torch.bfloat16)
+    ref = X.double().numpy() @ W.double().numpy().T
+    Y = torch.empty((M, N), dtype=torch.float32, device=dev())
+    sx.gemm_bf16(X.to(dev()), W.to(dev()), Y, mode=0)
+    torch.cuda.synchronize()
+    assert np.abs(Y.cpu().double().numpy() - ref).max() <= 1e-5 * np.sqrt(K) * np.abs(ref).max() + 1e-6
+
+
+@pytest.mark.parametrize("M,F,K", [(256, 128, 64), (300, 200, 256), (100, 11008, 128), (128, 96, 4096), (7, 40, 64)])
 def test_gemm_bf16_swiglu(sx, M, F, K):
     X = wl.hash_normal(3, (M, K), dtype=torch.bfloat16)
     Wg = wl.hash_normal(4, (F, K), std=0.1, dtype=torch.bfloat16)
