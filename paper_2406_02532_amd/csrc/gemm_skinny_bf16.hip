@@ -284,12 +284,13 @@ int sx_launch_gemm_skinny_bf16(const void* X, const void* W0, const void* W1, co
     a.N = n0 + n1 + n2;
     a.tilesN = (a.N + BN - 1) / BN;
   }
-  // two workgroups fit a compute unit: cut K while that leaves slots empty, parts of at least 4 slabs, and
-  // only as far as the caller's memory for partial sums (and its 256 counters) goes
+  // Cut K only while there are fewer tiles than compute units (measured: with a tile per unit or more the extra
+  // parts cost more in partial sums and short K loops than they gain), parts of at least 4 slabs, and only as
+  // far as the caller's memory for partial sums (and its 256 counters) goes
   a.split = 1;
   a.part = nullptr;
   a.part_cnt = nullptr;
-  const int slots = 2 * compute_units(), nb = K / BK;
+  const int slots = compute_units(), nb = K / BK;
   if (split_ws && a.tilesN <= 256 && 2 * a.tilesN <= slots) {
     int split = slots / a.tilesN;
     if (split > 8) split = 8;
