@@ -56,7 +56,7 @@ def main():
                          "of this command holds a dispatch of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'). "
+        print("bench.py measures one GPU: this build has no multi-GPU path. "
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 

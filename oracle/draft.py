@@ -25,8 +25,9 @@ from .expand import expand_topk
 from .model import verify_tree
 
 
-def create_draft_tree(cfg, w, prefix_k, prefix_v, root_token, K, D, B, k):
-    """Returns dict(tokens, parent, cum_logp (fp32, as the candidates' scores are), iterations)."""
+def create_draft_tree(cfg, w, prefix_k, prefix_v, root_token, K, D, B, k, act_round=None):
+    """Returns dict(tokens, parent, cum_logp (fp32, as the candidates' scores are), iterations).
+    act_round="bf16" evaluates the draft model as a bf16 model (see model.verify_tree)."""
     tokens, parent, cum = [], [], []
     heap = [(0.0, 0, int(root_token), -1)]          # (nll, entry number, token, parent node)
     entered = 1
@@ -49,7 +50,8 @@ def create_draft_tree(cfg, w, prefix_k, prefix_v, root_token, K, D, B, k):
         if len(tokens) >= K:
             T = float(np.sort(-np.asarray(cum, dtype=np.float64))[K - 1])
         # the whole tree goes through the oracle's forward; only the batch's rows are used
-        logits = verify_tree(cfg, w, prefix_k, prefix_v, np.asarray(tokens), np.asarray(parent))["logits"]
+        logits = verify_tree(cfg, w, prefix_k, prefix_v, np.asarray(tokens), np.asarray(parent),
+                             act_round=act_round)["logits"]
         sel = expand_topk(logits[batch].astype(np.float32), np.asarray([cum[i] for i in batch], dtype=np.float32),
                           min(k, cfg.vocab), min(K, len(batch) * min(k, cfg.vocab)))
         for row, tok, score in zip(sel["row"], sel["token"], sel["score"]):

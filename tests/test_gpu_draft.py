@@ -164,3 +164,40 @@ def test_speculative_generation_end_to_end_equals_sequential_sampling(sx, draft_
     assert checked >= 3
     if draft_kind == "self":
         assert accepted >= 3                 # drafting with the target itself must get draft tokens accepted
+
+
+def test_draft_tree_bf16_model_close_to_oracle(sx):
+    """The MFMA path of the draft loop (narrow-tile GEMMs with K cut in parts, 32-row attention tiles, rotation in a
+    kernel of its own, growing tree K/V in bf16) against the oracle evaluating the same bf16 model.  Two bf16
+    evaluations differ by rounding flips (a few 1e-3 in log-probability), which can swap candidates whose scores
+    nearly tie; so: scores of the nodes both trees contain agree to 0.05, and at least 90% of the nodes coincide."""
+    cfg = wl.ModelCfg(2, 512, 4, 2, 128, 1408, 2000, dtype="bf16")
+    w = wl.gen_weights(cfg, seed=81)
+    w = dict(w, lm_head=(w["lm_head"].float() * 12.0).to(torch.bfloat16), embed=(w["embed"].float() * 20.0).to(torch.bfloat16))
+    P = 40
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=82)
+    mw = sx.ModelWeights(cfg, weights_to(w, dev()))
+    K, D, B, k = 60, 6, 32, 6
+    ref = oracle.create_draft_tree(cfg, w, pk, pv, 11, K=K, D=D, B=B, k=k, act_round="bf16")
+    toks, par, cum, n, ws = sx.draft_tree(mw, pk.to(dev()), pv.to(dev()), P, torch.tensor([11], dtype=torch.int32, device=dev()),
+                                          K, D, B, k)
+    torch.cuda.synchronize()
+    assert sx.check_status(ws) == 0
+    n = int(n.item())
+    got = dict(tokens=toks[:n].cpu().numpy(), parent=par[:n].cpu().numpy(), cum_logp=cum[:n].cpu().numpy())
+
+    def paths(t):
+        out = {}
+        for i in range(len(t["tokens"])):
+            p, j = [], i
+            while j >= 0:
+                p.append(int(t["tokens"][j]))
+                j = int(t["parent"][j])
+            out[tuple(reversed(p))] = float(t["cum_logp"][i])
+        return out
+    a, b = paths(ref), paths(got)
+    common = set(a) & set(b)
+    assert n == len(ref["tokens"]) == K
+    assert len(common) >= 0.9 * K, (len(common), K)
+    assert max(abs(a[p] - b[p]) for p in common) <= 0.05
+    assert all(-1 <= got["parent"][i] < i for i in range(n))
