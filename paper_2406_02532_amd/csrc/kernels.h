@@ -61,7 +61,10 @@ int sx_launch_zero_i32(int32_t* p, int n, hipStream_t st);
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
                              const unsigned long long* rowmask, int T, int Tq, int P, int Hq, int Hkv, void* out,
-                             hipStream_t st);
+                             void* split_ws, size_t split_ws_bytes, hipStream_t st);
+// memory for the partial results when few query rows make the launch share the key tiles among workgroups
+// (used only for Tq <= Tq_max; split_ws may be null: no sharing)
+size_t sx_tree_attn_split_workspace(int Tq_max, int Hq);
 // Query nodes per attention workgroup: 128 rows / G, fewer (down to one wave's 32 rows) when there are so few
 // query nodes that the grid would leave most of the chip idle -- the draft model's small batches.  The
 // workspace is sized for the smallest value.

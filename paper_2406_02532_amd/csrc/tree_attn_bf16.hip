@@ -49,6 +49,10 @@ struct AttnArgs {
   const unsigned long long* rowmask;  // [T][W64]
   unsigned short* out;             // [T][Hq][128]
   int T, Tq, P, Hq, Hkv, G, npt, W64;  // T: nodes of the tree (klist stride); Tq: query nodes in q/out
+  // splits > 1: blockIdx.z takes a contiguous share of the key tiles and leaves, per query row, its
+  // unnormalised output, reference maximum and sum for attn_combine_kernel
+  int splits;
+  float *part_o, *part_m, *part_l;  // [splits][Tq * Hq][128], [splits][Tq * Hq] x 2
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -243,9 +247,11 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
 
   // Tile t lives in stage t % 2.  Top of an iteration: wait for this wave's copies of tile t, barrier
   // (everybody's are in, and everybody is done with tile t-1, whose stage the copies of tile t+1 go to).
-  const int nTiles = nPre + nTree;
-  if (nTiles > 0) { SX_FETCH(0, K0, V0) }
-  for (int t = 0; t < nTiles; t += 2) {
+  const int nAll = nPre + nTree;
+  const int tBeg = (int)((long long)blockIdx.z * nAll / a.splits);   // this workgroup's share of the key tiles
+  const int nTiles = (int)((long long)(blockIdx.z + 1) * nAll / a.splits);
+  if (tBeg < nTiles) { SX_FETCH(tBeg, K0, V0) }
+  for (int t = tBeg; t < nTiles; t += 2) {
     {
       SX_WAIT_BARRIER()
       const unsigned long long mask = rmask >> (4 * lh);
@@ -266,6 +272,24 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
 
   // ---- normalise and store -------------------------------------------------------------------------
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (a.splits > 1) {
+    if (row_ok) {
+      const size_t qrow = (size_t)node * a.Hq + head, nrow = (size_t)a.Tq * a.Hq;
+      float* po = a.part_o + ((size_t)blockIdx.z * nrow + qrow) * DH;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 w = {oacc[db][4 * g + 0], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(po + 32 * db + 8 * g + 4 * lh) = w;
+        }
+      if (lh == 0) {
+        a.part_m[(size_t)blockIdx.z * nrow + qrow] = m_ref;
+        a.part_l[(size_t)blockIdx.z * nrow + qrow] = l_tot;
+      }
+    }
+    return;
+  }
   if (row_ok && l_tot > 0.f) {
     const float inv = 1.0f / l_tot;
     unsigned short* op = a.out + ((size_t)node * a.Hq + head) * DH;
@@ -282,12 +306,37 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   }
 }
 
+// out[row][d] = sum_z O_z[row][d] 2^((m_z - M) c) / sum_z l_z 2^((m_z - M) c), M = max_z m_z: the softmax over all
+// keys put together from the shares of the key tiles (m_z = -inf, l_z = 0 for a share without keys of the row)
+__global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_m,
+                                                           const float* __restrict__ part_l, int splits, int nrow,
+                                                           unsigned short* __restrict__ out) {
+  const int row = blockIdx.x, d = threadIdx.x;
+  const float c2 = kLog2e * 0.08838834764831845f;
+  float M = -__builtin_huge_valf();
+  for (int z = 0; z < splits; ++z) M = fmaxf(M, part_m[(size_t)z * nrow + row]);
+  float num = 0.f, den = 0.f;
+  for (int z = 0; z < splits; ++z) {
+    const float m = part_m[(size_t)z * nrow + row];
+    if (m == -__builtin_huge_valf()) continue;
+    const float wgt = __builtin_amdgcn_exp2f((m - M) * c2);
+    num += part_o[((size_t)z * nrow + row) * DH + d] * wgt;
+    den += part_l[(size_t)z * nrow + row] * wgt;
+  }
+  out[(size_t)row * DH + d] = den > 0.f ? (unsigned short)f32_to_bf16_bits(num / den) : (unsigned short)0;
+}
+
 }  // namespace
+
+size_t sx_tree_attn_split_workspace(int Tq_max, int Hq) {
+  return (size_t)8 * Tq_max * Hq * (DH + 2) * sizeof(float);
+}
 
 int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tree, const void* k_prefix,
                              const void* v_prefix, const int32_t* klist, const int32_t* kcnt,
                              const unsigned long long* rowmask, int T, int Tq, int P, int Hq, int Hkv, void* out,
-                             hipStream_t st) {
+                             void* split_ws, size_t split_ws_bytes, hipStream_t st) {
   const int G = Hq / Hkv;
   if (Hq % Hkv != 0 || !(G == 1 || G == 2 || G == 4 || G == 8)) return SX_ERR_SHAPE;
   // the copies address rows with 32-bit byte offsets from the start of each K/V array
@@ -311,7 +360,29 @@ int sx_launch_tree_attn_bf16(const void* q, const void* k_tree, const void* v_tr
   a.npt = sx_attn_nodes_per_tile(Hq, Hkv, Tq);  // the same value the tile lists were built with
   a.W64 = (T + 63) / 64;
   dim3 grid((Tq + a.npt - 1) / a.npt, Hkv);
+  // few query rows (a batch of the draft model): the grid leaves most of the chip idle while each workgroup
+  // walks all key tiles one after the other; give shares of the key tiles to up to 8 workgroups instead
+  a.splits = 1;
+  a.part_o = a.part_m = a.part_l = nullptr;
+  const int wgs = (int)(grid.x * grid.y), npre = (P + KTILE - 1) / KTILE;
+  if (split_ws && wgs < 256 && npre >= 4) {
+    int s = 512 / wgs;
+    if (s > 8) s = 8;
+    if (s > npre / 2) s = npre / 2;
+    const size_t nrow = (size_t)Tq * Hq;
+    if (s > 1 && split_ws_bytes >= (size_t)s * nrow * (DH + 2) * sizeof(float)) {
+      a.splits = s;
+      a.part_o = static_cast<float*>(split_ws);
+      a.part_m = a.part_o + (size_t)s * nrow * DH;
+      a.part_l = a.part_m + (size_t)s * nrow;
+    }
+  }
+  grid.z = a.splits;
   tree_attn_bf16_kernel<<<grid, kThreads, 0, st>>>(a);
   SX_LAUNCH_CHECK();
+  if (a.splits > 1) {
+    attn_combine_kernel<<<Tq * Hq, 128, 0, st>>>(a.part_o, a.part_m, a.part_l, a.splits, Tq * Hq, a.out);
+    SX_LAUNCH_CHECK();
+  }
   return SX_OK;
 }

@@ -28,6 +28,8 @@ struct Layout {
   void *x, *q, *o, *act, *tk, *tv;
   void* split_ws;
   size_t split_bytes;
+  void* attn_split_ws;
+  size_t attn_split_bytes;
   size_t bytes;
 };
 
@@ -47,6 +49,9 @@ Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
   L.qkv = cv.take<float>((size_t)T * (Nq + 2 * Nkv));  // fp32 QKV of the paths that rotate in a kernel of their own
   L.split_bytes = c.dtype == SX_BF16 ? sx_gemm_split_workspace() : 0;  // K-split counters and partial sums of the GEMMs
   L.split_ws = L.split_bytes ? cv.take<char>(L.split_bytes) : nullptr;
+  // partial attention results of small batches (at most 128 query nodes) that share the key tiles among workgroups
+  L.attn_split_bytes = c.dtype == SX_BF16 ? sx_tree_attn_split_workspace(T < 128 ? T : 128, c.n_q_heads) : 0;
+  L.attn_split_ws = L.attn_split_bytes ? cv.take<char>(L.attn_split_bytes) : nullptr;
   L.q = cv.take<char>((size_t)T * Nq * es);
   L.tk = cv.take<char>((size_t)T * Nkv * es);
   L.tv = cv.take<char>((size_t)T * Nkv * es);
@@ -195,7 +200,7 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
       SX_TIMED(SX_K_ROPE, sx_launch_rope_split(L.qkv, rope_cs, n, Hq, Hkv, Dh, c.dtype, L.q, tk, tv, st));
     if (bf) {
       SX_TIMED(SX_K_ATTN, sx_launch_tree_attn_bf16(L.q, tkb, tvb, pk, pv, L.klist, L.kcnt, L.rowmask, T, n, P, Hq, Hkv,
-                                                   L.o, st));
+                                                   L.o, n <= 128 ? L.attn_split_ws : nullptr, L.attn_split_bytes, st));
       SX_TIMED(SX_K_GEMM_O,
                sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, n, Nq, SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
       SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
@@ -340,7 +345,7 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
                              static_cast<int32_t*>(workspace), st));
   SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, 0, L.klist, L.kcnt, L.rowmask, st));
   return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, T, P, n_q_heads,
-                                  n_kv_heads, out, st);
+                                  n_kv_heads, out, nullptr, 0, st);
 }
 
 // cos/sin table, then (256-byte aligned) the K-split counters and partial sums of the GEMM

@@ -254,7 +254,7 @@ def test_bf16_tree_verified_in_batches_matches_one_pass(sx):
     flip-noise floor is 2.4e-2), with 99% of the logits within half of it."""
     cfg = wl.ModelCfg(4, 1024, 8, 2, 128, 2752, 4000, dtype="bf16")
     w = wl.gen_weights(cfg, seed=41)
-    P = 70
+    P = 600           # ten key tiles of prefix: batches of few nodes share them among several workgroups
     pk, pv = wl.gen_prefix_kv(cfg, P, seed=42)
     tok, par, _ = wl.gen_best_first_tree(150, 6, cfg.vocab, seed=43)
     T = len(tok)
@@ -274,7 +274,15 @@ def test_bf16_tree_verified_in_batches_matches_one_pass(sx):
         rows.append(lg.cpu().double().numpy())
     got = np.concatenate(rows, axis=0)
     diff = np.abs(got - one)
-    assert diff.max() <= TOL_BF16 and np.quantile(diff, 0.99) <= 1e-2, (diff.max(), np.quantile(diff, 0.99))
+    # both against the oracle's bf16 evaluation, to the bar of the one-pass tests: 99.99% within 2e-2, the worst
+    # within twice the oracle's own flip-noise floor; and against each other, two valid evaluations, the same
+    ref = oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16")["logits"]
+    floor = np.abs(oracle.verify_tree(cfg, w, pk, pv, tok, par, act_round="bf16", perturb=3e-6)["logits"] - ref).max()
+    for name, x in (("batches", got), ("one pass", one)):
+        e = np.abs(x - ref)
+        print(f"[{name}] max|gpu-oracle|={e.max():.3e}, 99.99th pct {np.quantile(e, 0.9999):.3e}; floor {floor:.3e}")
+        _assert_bf16_parity(float(e.max()), float(np.quantile(e, 0.9999)), float(floor))
+    assert diff.max() <= max(TOL_BF16, 2.0 * floor) and np.quantile(diff, 0.99) <= 1e-2, (diff.max(), np.quantile(diff, 0.99))
 
 
 def test_commit_kv_bf16_gathers_path_rows(sx):
