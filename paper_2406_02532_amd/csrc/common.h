@@ -34,6 +34,38 @@ static inline size_t sx_align_up(size_t v, size_t a) { return (v + a - 1) / a * 
     if (hipGetLastError() != hipSuccess) return SX_ERR_HIP; \
   } while (0)
 
+// returns the callee's status from the caller unless it is SX_OK
+#define SX_TRY(expr)                         \
+  do {                                       \
+    const int rc_ = (expr);                  \
+    if (rc_ != SX_OK) return rc_;            \
+  } while (0)
+
+// Hands out 256-byte aligned pieces of a workspace; with a null base it only adds up sizes.
+struct SxCarver {
+  uintptr_t base;
+  size_t off;
+  SxCarver(void* p, size_t first) : base(reinterpret_cast<uintptr_t>(p)), off(first) {}
+  template <typename T>
+  T* take(size_t n) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += sx_align_up(n * sizeof(T), 256);
+    return p;
+  }
+};
+
+// compute units of the current device (256 if the runtime cannot tell)
+static inline int sx_compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+  }
+  return n;
+}
+
 // ---- bf16 <-> fp32 bit helpers ------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {  // round to nearest even (hardware cvt)

@@ -18,12 +18,6 @@
 #include "kernels.h"
 #include "../../include/specexec_mi.h"
 
-#define SX_TRY(expr)          \
-  do {                        \
-    const int rc_ = (expr);   \
-    if (rc_ != SX_OK) return rc_; \
-  } while (0)
-
 namespace {
 
 constexpr int kThreads = 1024;
@@ -246,18 +240,6 @@ struct DraftLayout {
   int S, logcap, hcap, ksel, bsel;
 };
 
-struct Carver {
-  uintptr_t base;
-  size_t off;
-  explicit Carver(void* p) : base(reinterpret_cast<uintptr_t>(p)), off(0) {}
-  template <typename T>
-  T* take(size_t n) {
-    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
-    off += sx_align_up(n * sizeof(T), 256);
-    return p;
-  }
-};
-
 bool draft_shape_ok(const sx_model_cfg& c, int P, int K, int D, int B, int k) {
   if (K < 1 || D < 1 || B < 1 || k < 1) return false;
   const long long S = (long long)D * B;
@@ -270,7 +252,7 @@ bool draft_shape_ok(const sx_model_cfg& c, int P, int K, int D, int B, int k) {
 }
 
 DraftLayout draft_carve(const sx_model_cfg& c, int P, int K, int D, int B, int k, void* ws) {
-  Carver cv(ws);
+  SxCarver cv(ws, 0);
   DraftLayout L;
   L.S = D * B;
   L.ksel = k < c.vocab ? k : c.vocab;

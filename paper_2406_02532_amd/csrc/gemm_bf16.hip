@@ -483,16 +483,6 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 }
 #undef SX_WAIT_BARRIER
 
-int compute_units() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-      n = 256;
-  }
-  return n;
-}
 
 // Decides whether the last tiles get a K split: only when there are more tiles than compute units with a
 // remainder that would fill at most half of the chip for a whole round, and the caller gave memory for the
@@ -504,7 +494,7 @@ void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   a.part = nullptr;
   a.part_cnt = nullptr;
   a.full_tiles = a.tail_items = a.full_per_xcd = a.tail_per_xcd = 0;
-  const int cus = compute_units(), tiles = a.tilesM * a.tilesN, nb = a.K / BK;
+  const int cus = sx_compute_units(), tiles = a.tilesM * a.tilesN, nb = a.K / BK;
   if (!split_ws || tiles <= cus) return;
   const int rest = tiles % cus;
   if (rest == 0 || 2 * rest > cus) return;
@@ -573,7 +563,7 @@ int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const voi
 }
 
 // 1 KB of counters (at most 256 split tiles, zero before the first launch) and one partial tile per compute unit
-size_t sx_gemm_split_workspace() { return 1024 + (size_t)compute_units() * BM * BN * sizeof(float); }
+size_t sx_gemm_split_workspace() { return 1024 + (size_t)sx_compute_units() * BM * BN * sizeof(float); }
 
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
                                  const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,

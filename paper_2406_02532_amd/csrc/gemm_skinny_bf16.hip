@@ -247,16 +247,6 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
 }
 #undef SX_WAIT_BARRIER
 
-int compute_units() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-      n = 256;
-  }
-  return n;
-}
 
 }  // namespace
 
@@ -290,7 +280,7 @@ int sx_launch_gemm_skinny_bf16(const void* X, const void* W0, const void* W1, co
   a.split = 1;
   a.part = nullptr;
   a.part_cnt = nullptr;
-  const int slots = compute_units(), nb = K / BK;
+  const int slots = sx_compute_units(), nb = K / BK;
   if (split_ws && a.tilesN <= 256 && 2 * a.tilesN <= slots) {
     int split = slots / a.tilesN;
     if (split > 8) split = 8;

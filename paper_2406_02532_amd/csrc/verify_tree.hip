@@ -8,18 +8,6 @@
 namespace {
 
 // Hands out 256-byte aligned slices of the workspace; with a null base it only measures.
-struct Carver {
-  uintptr_t base;
-  size_t off;
-  explicit Carver(void* p) : base(reinterpret_cast<uintptr_t>(p)), off(SX_WS_HEADER) {}
-  template <typename T>
-  T* take(size_t n) {
-    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
-    off += sx_align_up(n * sizeof(T), 256);
-    return p;
-  }
-};
-
 struct Layout {
   int32_t *tok_s, *par_s, *depth, *klist, *kcnt;
   float2* rope_cs;
@@ -36,7 +24,7 @@ struct Layout {
 // One function lays the workspace out, for the size query (base == nullptr) and for the run.
 Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
   (void)P;
-  Carver cv(ws);
+  SxCarver cv(ws, SX_WS_HEADER);
   Layout L;
   const size_t es = c.dtype == SX_BF16 ? 2 : 4;
   const size_t Nq = (size_t)c.n_q_heads * c.head_dim, Nkv = (size_t)c.n_kv_heads * c.head_dim;
@@ -90,11 +78,6 @@ int check_cfg(const sx_model_cfg& c, int P, int T) {
   return SX_OK;
 }
 
-#define SX_TRY(expr)          \
-  do {                        \
-    const int rc_ = (expr);   \
-    if (rc_ != SX_OK) return rc_; \
-  } while (0)
 // same, bracketed by the optional event timer
 #define SX_TIMED(tag, expr)   \
   do {                        \
@@ -304,7 +287,7 @@ struct AttnLayout {
   size_t bytes;
 };
 AttnLayout carve_attn(int T, int npt, void* ws) {
-  Carver cv(ws);
+  SxCarver cv(ws, SX_WS_HEADER);
   AttnLayout L;
   const size_t tiles = (T + npt - 1) / npt;
   L.tok_s = cv.take<int32_t>(T);
