@@ -201,3 +201,26 @@ def test_draft_tree_bf16_model_close_to_oracle(sx):
     assert len(common) >= 0.9 * K, (len(common), K)
     assert max(abs(a[p] - b[p]) for p in common) <= 0.05
     assert all(-1 <= got["parent"][i] < i for i in range(n))
+
+
+def test_draft_tree_degenerate_budgets(sx, draft):
+    """K = 1 (the root alone), one iteration, no cached prefix: the smallest trees the loop can return."""
+    cfg, w, wn, pk, pv = draft
+    mw = sx.ModelWeights(cfg, weights_to(w, dev()))
+    root = torch.tensor([42], dtype=torch.int32, device=dev())
+    toks, par, cum, n, ws = sx.draft_tree(mw, None, None, 0, root, 1, 3, 4, 2)          # K = 1
+    torch.cuda.synchronize()
+    assert sx.check_status(ws) == 0 and int(n.item()) == 1
+    assert toks[:1].cpu().tolist() == [42] and par[:1].cpu().tolist() == [-1] and float(cum[0]) == 0.0
+    ref = oracle.create_draft_tree(cfg, wn, np.zeros((cfg.n_layers, 0, cfg.n_kv_heads, cfg.head_dim)),
+                                   np.zeros((cfg.n_layers, 0, cfg.n_kv_heads, cfg.head_dim)), 42, K=6, D=1, B=8, k=3)
+    toks, par, cum, n, ws = sx.draft_tree(mw, None, None, 0, root, 6, 1, 8, 3)          # D = 1: only the root is expanded
+    torch.cuda.synchronize()
+    assert int(n.item()) == len(ref["tokens"]) == 1
+    ref = oracle.create_draft_tree(cfg, wn, np.zeros((cfg.n_layers, 0, cfg.n_kv_heads, cfg.head_dim)),
+                                   np.zeros((cfg.n_layers, 0, cfg.n_kv_heads, cfg.head_dim)), 42, K=5, D=2, B=8, k=3)
+    toks, par, cum, n, ws = sx.draft_tree(mw, None, None, 0, root, 5, 2, 8, 3)          # root + its 3 best children
+    torch.cuda.synchronize()
+    n = int(n.item())
+    assert n == len(ref["tokens"]) == 4
+    assert toks[:n].cpu().tolist() == ref["tokens"].tolist() and par[:n].cpu().tolist() == ref["parent"].tolist()

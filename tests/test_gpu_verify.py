@@ -285,6 +285,31 @@ def test_bf16_tree_verified_in_batches_matches_one_pass(sx):
     assert diff.max() <= max(TOL_BF16, 2.0 * floor) and np.quantile(diff, 0.99) <= 1e-2, (diff.max(), np.quantile(diff, 0.99))
 
 
+def test_range_and_round_edge_cases(sx, c1):
+    """One node at a time into a tree buffer larger than the tree; host-side shape errors of the new calls."""
+    cfg, w, wn, pk, pv = c1
+    P = pk.shape[1]
+    mw = sx.ModelWeights(cfg, weights_to(w, dev()))
+    tok, par = wl.gen_chain_tree(6, cfg.vocab, seed=4)
+    ref = oracle.verify_tree(cfg, wn, pk, pv, tok, par)["logits"]
+    pkd, pvd = to_dev(torch.as_tensor(pk), torch.float32), to_dev(torch.as_tensor(pv), torch.float32)
+    tree_k = torch.zeros((cfg.n_layers, 20, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device=dev())
+    tree_v = torch.zeros_like(tree_k)
+    for i in range(6):                                               # a chain grown one token at a time = decoding
+        lg, ws = sx.verify_tree_range(mw, pkd, pvd, P, to_dev(tok[:i + 1]), to_dev(par[:i + 1]), i, tree_k, tree_v)
+        torch.cuda.synchronize()
+        assert sx.check_status(ws) == 0 and lg.shape[0] == 1
+        assert np.abs(lg.cpu().double().numpy()[0] - ref[i]).max() <= 1e-4
+    with pytest.raises(sx.SxError):                                  # first node beyond the tree
+        sx.verify_tree_range(mw, pkd, pvd, P, to_dev(tok), to_dev(par), 6, tree_k, tree_v)
+    small_k = torch.zeros((cfg.n_layers, 4, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device=dev())
+    with pytest.raises(sx.SxError):                                  # tree buffers smaller than the tree
+        sx.verify_tree_range(mw, pkd, pvd, P, to_dev(tok), to_dev(par), 2, small_k, small_k.clone())
+    buf = sx.RoundBuffers(mw, P + 6, 6)
+    with pytest.raises(sx.SxError):                                  # the cache has no room for the round's nodes
+        sx.specexec_round(mw, pkd, pvd, P, to_dev(tok), to_dev(par), 0.6, 0.9, 1, buf)
+
+
 def test_commit_kv_bf16_gathers_path_rows(sx):
     """sx_commit_kv alone, bf16 rows of 2 KB, n read from the device: byte-exact gather, rows past n untouched."""
     cfg = wl.ModelCfg(3, 1024, 8, 8, 128, 2752, 4000, dtype="bf16")
