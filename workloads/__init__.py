@@ -7,6 +7,6 @@ oracle and the HIP library can be handed the very same bytes.
 """
 from .gen import (  # noqa: F401
     ModelCfg, CONFIGS, hash_normal, gen_weights, gen_prefix_kv, gen_tokens,
-    gen_uniform_tree, gen_best_first_tree, gen_chain_tree, gen_expand_inputs,
+    gen_uniform_tree, gen_best_first_tree, gen_chain_tree, gen_expand_inputs, gen_w4,
     gen_crafted_logits, tree_stats,
 )

@@ -317,3 +317,18 @@ def gen_crafted_logits(tokens: np.ndarray, parent: np.ndarray, V: int, seed: int
             c = kids[i][int(r.integers(0, len(kids[i])))]
             logits[i, tokens[c]] = np.float32(boost) + (np.float32(0.0) if sharp else logits[i, tokens[c]])
     return logits
+
+
+# ----------------------------------------------------------------------------------
+# 4-bit group-quantised weights (storage only: random codes, scales and zero points)
+# ----------------------------------------------------------------------------------
+
+
+def gen_w4(N: int, K: int, group: int, seed: int):
+    """Random quantised matrix: qweight uint32 [N][K/8] (eight 4-bit codes per word), scales bf16 [N][K/group]
+    (0.002 .. 0.02), zeros uint8 [N][K/group] (0 .. 15).  numpy Philox; returns torch tensors on the CPU."""
+    r = np.random.Generator(np.random.Philox(seed))
+    qweight = r.integers(0, 2 ** 32, size=(N, K // 8), dtype=np.uint64).astype(np.uint32)
+    scales = torch.from_numpy(r.uniform(0.002, 0.02, size=(N, K // group)).astype(np.float32)).to(torch.bfloat16)
+    zeros = torch.from_numpy(r.integers(0, 16, size=(N, K // group), dtype=np.int64).astype(np.uint8))
+    return torch.from_numpy(qweight.view(np.int32)), scales, zeros
