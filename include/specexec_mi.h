@@ -277,6 +277,18 @@ int sx_qkv_rope_bf16(const void *X, const void *Wq, const void *Wk, const void *
                      const int32_t *positions, float rope_base, void *q_out, void *k_out,
                      void *v_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Y = X W^T for a small batch (M <= 128) with 4-bit group-quantised weights (Sect. 5: the paper's fastest
+ * setting runs the models quantised to 4 bits): dequantisation in registers on the way to the matrix cores.
+ * X device bf16 [M][K]; qweight device uint32 [N][K/8], eight 4-bit codes per word, code j of word i of a
+ * row being k = 8 i + j in bits 4j..4j+3; scales device bf16 [N][K/group]; zeros device uint8 [N][K/group],
+ * values 0..15; w = bf16(scale * (code - zero)).  group a power of two >= 64, K % group == 0.  mode 0: Y float
+ * [M][N] = X W^T; mode 1: Y += X W^T.  workspace: NULL, or device memory of sx_gemm_w4a16_workspace()
+ * bytes, 256-byte aligned (lets launches with few column tiles cut K among workgroups); caller-owned. */
+size_t sx_gemm_w4a16_workspace(void);
+int sx_gemm_w4a16_bf16(const void *X, const void *qweight, const void *scales, const void *zeros, void *Y,
+                       int32_t M, int32_t N, int32_t K, int32_t group, int32_t mode, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
 /* Tree attention alone (App. D merged mask), bf16: q device bf16 [T][Hq][128], tree K/V
  * [T][Hkv][128], prefix K/V [P][Hkv][128], out device bf16 [T][Hq][128]; n_q_heads/n_kv_heads in {1,2,4,8}.  workspace sized by
  * sx_tree_attention_workspace. */

@@ -363,6 +363,28 @@ def test_gemm_bf16_llama3_vocabulary_head(sx, M):
     assert np.abs(Y.cpu().double().numpy() - ref).max() <= 1e-5 * np.sqrt(K) * np.abs(ref).max() + 1e-6
 
 
+@pytest.mark.parametrize("M,N,K,group,split", [(128, 4096, 4096, 128, True), (128, 256, 11008, 64, True),
+                                               (37, 200, 256, 128, False), (1, 64, 64, 64, False),
+                                               (100, 12288, 512, 128, True)])
+def test_gemm_w4a16(sx, M, N, K, group, split):
+    """4-bit group-quantised weights dequantised in registers: against the oracle's product with the weights it
+    dequantises by the stated formula (bf16(scale * (code - zero))); with and without K cut among workgroups,
+    store and accumulate."""
+    X = wl.hash_normal(31, (M, K), dtype=torch.bfloat16)
+    qw, sc, zr = wl.gen_w4(N, K, group, seed=32)
+    ref = oracle.gemm_w4a16(X, qw.numpy().view(np.uint32), sc.double().numpy(), zr.numpy(), group)
+    Y = torch.full((M, N), 3.0, dtype=torch.float32, device=dev())
+    ws = torch.empty(sx.lib.sx_gemm_w4a16_workspace(), dtype=torch.uint8, device=dev()) if split else None
+    args = (X.to(dev()), qw.to(dev()), sc.to(dev()), zr.to(dev()))
+    sx.gemm_w4a16_bf16(*args, Y, group, mode=0, workspace=ws)
+    torch.cuda.synchronize()
+    tol = 1e-5 * np.sqrt(K) * np.abs(ref).max() + 1e-6
+    assert np.abs(Y.cpu().double().numpy() - ref).max() <= tol
+    sx.gemm_w4a16_bf16(*args, Y, group, mode=1, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.abs(Y.cpu().double().numpy() - 2 * ref).max() <= 2 * tol
+
+
 @pytest.mark.parametrize("M,F,K", [(256, 128, 64), (300, 200, 256), (100, 11008, 128), (128, 96, 4096), (7, 40, 64)])
 def test_gemm_bf16_swiglu(sx, M, F, K):
     X = wl.hash_normal(3, (M, K), dtype=torch.bfloat16)
