@@ -12,7 +12,7 @@ EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached"
            "sx_specexec_round_workspace", "sx_specexec_round", "sx_draft_tree_workspace", "sx_draft_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_gemm_w4a16_workspace", "sx_gemm_w4a16_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
-           "sx_profile_enable", "sx_profile_disable", "sx_profile_read"]
+           "sx_profile_enable", "sx_profile_select", "sx_profile_disable", "sx_profile_read"]
 
 SX_F32, SX_BF16 = 0, 1
 
@@ -96,6 +96,8 @@ def _load():
     L.sx_tree_attention_bf16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     L.sx_profile_enable.restype = C.c_int
     L.sx_profile_enable.argtypes = [i32]
+    L.sx_profile_select.restype = C.c_int
+    L.sx_profile_select.argtypes = [i32]
     L.sx_profile_disable.restype = C.c_int
     L.sx_profile_read.restype = C.c_int
     L.sx_profile_read.argtypes = [vp, vp, i32, vp]
@@ -363,6 +365,12 @@ def check_status(workspace, stream=None) -> int:
 
 def profile_enable(max_records: int):
     _check(lib.sx_profile_enable(max_records), "sx_profile_enable")
+
+
+def profile_select(kernel_class: str = ""):
+    """Time only launches of the named kernel class (a value of KERNEL_CLASSES; "" = all)."""
+    code = 0 if not kernel_class else {v: k for k, v in KERNEL_CLASSES.items()}[kernel_class]
+    _check(lib.sx_profile_select(code), "sx_profile_select")
 
 
 def profile_disable():

@@ -7,20 +7,21 @@
 
 namespace {
 struct Prof {
-  bool on = false;
-  int cap = 0, n = 0;
+  bool on = false, skip = false;
+  int cap = 0, n = 0, only = 0;  // only != 0: time launches of that kernel class alone
   std::vector<hipEvent_t> beg, end;
   std::vector<int> tag;
 } g_prof;
 }  // namespace
 
 void sx_prof_begin(int tag, hipStream_t st) {
-  if (!g_prof.on || g_prof.n >= g_prof.cap) return;
+  g_prof.skip = g_prof.only != 0 && tag != g_prof.only;
+  if (!g_prof.on || g_prof.skip || g_prof.n >= g_prof.cap) return;
   g_prof.tag[g_prof.n] = tag;
   (void)hipEventRecord(g_prof.beg[g_prof.n], st);
 }
 void sx_prof_end(hipStream_t st) {
-  if (!g_prof.on || g_prof.n >= g_prof.cap) return;
+  if (!g_prof.on || g_prof.skip || g_prof.n >= g_prof.cap) return;
   (void)hipEventRecord(g_prof.end[g_prof.n], st);
   ++g_prof.n;
 }
@@ -38,6 +39,12 @@ extern "C" int sx_profile_enable(int32_t max_records) {
   }
   g_prof.n = 0;
   g_prof.on = true;
+  return SX_OK;
+}
+
+extern "C" int sx_profile_select(int32_t kernel_class) {
+  if (kernel_class < 0) return SX_ERR_SHAPE;
+  g_prof.only = kernel_class;
   return SX_OK;
 }
 
