@@ -503,6 +503,15 @@ def test_bf16_narrow_four_layer_model(sx):
     _assert_bf16_parity(err, q, floor)
 
 
+def test_bf16_small_tree_takes_the_narrow_kernels(sx):
+    """A tree of 100 nodes (at most 128 rows): the narrow-tile GEMMs with K cut among workgroups, the rotation
+    in a kernel of its own and attention tiles of fewer rows, against the oracle, to the same bar."""
+    cfg = wl.ModelCfg(4, 1024, 8, 2, 128, 2752, 4000, dtype="bf16")
+    err, q, floor, std = _bf16_model_parity(sx, cfg, P=700, T=100, k=8, seed=25)
+    assert std > 0.3
+    _assert_bf16_parity(err, q, floor)
+
+
 def test_c2_llama7b_layer_full_parity(sx):
     c = wl.CONFIGS["C2"]
     err, q, floor, std = _bf16_model_parity(sx, c["cfg"], c["P"], c["T"], c["k"], seed=31)
