@@ -486,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 
 // Decides whether the last tiles get a K split: only when there are more tiles than compute units with a
 // remainder that would fill at most half of the chip for a whole round, and the caller gave memory for the
-// partial sums; at most 4 ways, parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
+// partial sums; 2 ways, parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
 // small M, the draft model's batches -- was measured too: the partial sums, 256 KB per part, then outweigh
 // the weights being streamed, and the launch gets slower; such shapes want narrower tiles, not a K split.)
 void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
@@ -499,7 +499,7 @@ void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   const int rest = tiles % cus;
   if (rest == 0 || 2 * rest > cus) return;
   int split = cus / rest;
-  if (split > 4) split = 4;
+  if (split > 2) split = 2;  // measured at the 70B QKV shape: 2 ways 325 us, 3 ways 338, 4 ways 335 (uncut: 372)
   while (split > 1 && nb / split < 8) --split;
   if (split < 2 || rest > 256) return;
   if (split_ws_bytes < 1024 + (size_t)rest * split * BM * BN * sizeof(float)) return;

@@ -401,7 +401,7 @@ def test_gemm_bf16_swiglu(sx, M, F, K):
 
 
 # the last three shapes give more output tiles than the chip has compute units with a small remainder: the
-# remainder tiles are cut along K (4, 4 and 2 ways) and their partial sums added up by the last workgroup to arrive
+# remainder tiles are cut along K and their partial sums added up by the last workgroup to arrive
 @pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2),
                                         (2048, 2048, 64, 8), (2048, 2048, 64, 1), (2304, 1024, 64, 8)])
 def test_qkv_projection_with_rotary_epilogue(sx, T, d, Hq, Hkv):
