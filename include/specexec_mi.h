@@ -178,6 +178,21 @@ int sx_expand_topk(const float *logits, const float *cum_logp, int32_t N, int32_
                    int32_t B, int32_t *out_row, int32_t *out_token, float *out_cum_logp,
                    int32_t *n_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* sx_expand_topk for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, results and kernels as
+ * sx_expand_topk, but the N*k candidates are staged in a fixed device array that is part of the library
+ * (3 x 4 bytes per candidate, 768 KB in all, held by every GPU the library runs on until the process ends).
+ * Limit: N * k <= SX_EXPAND_STATIC_MAX_CANDIDATES (the paper-sized expansion step, 2048 nodes x 32
+ * tokens, just fits); larger calls return SX_ERR_SHAPE and belong to sx_expand_topk.  The call allocates
+ * and frees nothing and uses no allocating library routine; the first call on a device looks up that
+ * device's copy of the array (make the device current before calling).  All calls on one GPU share the
+ * array: calls that overlap on one GPU (two streams, two threads) race; calls on one stream are ordered
+ * and need no clearing between them, since every entry a call reads it has written itself. */
+#define SX_EXPAND_STATIC_MAX_CANDIDATES 65536
+int sx_expand_topk_static(const float *logits, const float *cum_logp, int32_t N, int32_t V, int32_t k,
+                          int32_t B, int32_t *out_row, int32_t *out_token, float *out_cum_logp,
+                          int32_t *n_out, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * sx_commit_kv -- Alg. 1, end of the loop body: the tokens the walk accepted join the
  * context.  Copies the keys and values of the visited nodes into the prefix cache:

@@ -10,7 +10,7 @@ import torch
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
 EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
            "sx_specexec_round_workspace", "sx_specexec_round", "sx_draft_tree_workspace", "sx_draft_tree", "sx_accept_walk_workspace", "sx_accept_walk",
-           "sx_expand_topk_workspace", "sx_expand_topk", "sx_check_status", "sx_status_string", "sx_version",
+           "sx_expand_topk_workspace", "sx_expand_topk", "sx_expand_topk_static", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_gemm_w4a16_workspace", "sx_gemm_w4a16_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
            "sx_profile_enable", "sx_profile_select", "sx_profile_disable", "sx_profile_read"]
 
@@ -73,6 +73,8 @@ def _load():
     L.sx_expand_topk_workspace.argtypes = [i32, i32, i32, i32]
     L.sx_expand_topk.restype = C.c_int
     L.sx_expand_topk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.sx_expand_topk_static.restype = C.c_int
+    L.sx_expand_topk_static.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     L.sx_check_status.restype = C.c_int
     L.sx_check_status.argtypes = [vp, vp]
     L.sx_status_string.restype = C.c_char_p
@@ -301,6 +303,16 @@ def expand_topk(logits, cum_logp, k: int, B: int, out_row=None, out_token=None, 
                             _ptr(n_out), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "sx_expand_topk")
     return out_row, out_token, out_cum_logp, n_out, workspace
+
+
+def expand_topk_static(logits, cum_logp, k: int, B: int, out_row, out_token, out_cum_logp, n_out, stream=None):
+    """sx_expand_topk_static: the expansion step with the library's own fixed scratch; the caller brings every
+    output (this wrapper allocates nothing either)."""
+    N, V = logits.shape
+    rc = lib.sx_expand_topk_static(_ptr(logits), _ptr(cum_logp), N, V, k, B, _ptr(out_row), _ptr(out_token),
+                                   _ptr(out_cum_logp), _ptr(n_out), _stream(stream))
+    _check(rc, "sx_expand_topk_static")
+    return out_row, out_token, out_cum_logp, n_out
 
 
 def row_logsoftmax_topk(logits, k: int, topk_logp=None, topk_idx=None, stream=None):

@@ -576,20 +576,29 @@ extern "C" size_t sx_expand_topk_workspace(int32_t N, int32_t V, int32_t k, int3
   return SX_WS_HEADER + 3 * nk;
 }
 
-extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_t N, int32_t V, int32_t k, int32_t B,
-                              int32_t* out_row, int32_t* out_token, float* out_cum_logp, int32_t* n_out,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-  if (!logits || !cum_logp || !out_row || !out_token || !out_cum_logp || !n_out) return SX_ERR_NULL;
-  if (!row_shape_ok(N, V, k) || B < 1 || B > 8192) return SX_ERR_SHAPE;
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) ||
-      workspace_bytes < sx_expand_topk_workspace(N, V, k, B))
-    return SX_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
-  const size_t nk = sx_align_up((size_t)N * (size_t)k * 4, 256);
-  char* ws = static_cast<char*>(workspace);
-  float* score = reinterpret_cast<float*>(ws + SX_WS_HEADER);
-  float* lp = reinterpret_cast<float*>(ws + SX_WS_HEADER + nk);
-  int* idx = reinterpret_cast<int*>(ws + SX_WS_HEADER + 2 * nk);
+namespace {
+
+// B = 8192 needs the full 64 KB of dynamic LDS next to the static arrays; set once per device
+int configure_select_once() {
+  static bool configured[64] = {};
+  int dev = 0;
+  SX_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return SX_ERR_HIP;
+  if (configured[dev]) return SX_OK;
+  SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
+  SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
+  configured[dev] = true;
+  return SX_OK;
+}
+
+// both kernels of the expansion step on `st`; score / lp / idx hold N*k entries each (every one of them is
+// written by the first kernel before the second reads it: nothing has to be cleared)
+int expand_topk_run(const float* logits, const float* cum_logp, int N, int V, int k, int B, int* out_row,
+                    int* out_token, float* out_cum_logp, int* n_out, float* score, float* lp, int* idx,
+                    hipStream_t st) {
+  SX_TRY(configure_select_once());
   sx_prof_begin(SX_K_ROW_TOPK, st);
   const int rc = row_topk_dispatch(logits, cum_logp, N, V, k, lp, idx, score, st);
   sx_prof_end(st);
@@ -600,14 +609,6 @@ extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_
   int nsort = 2;
   while (nsort < Bsel) nsort <<= 1;
   const size_t shmem = (size_t)nsort * sizeof(unsigned long long);
-  static bool configured = false;  // B = 8192 needs the full 64 KB of dynamic LDS next to the static arrays
-  if (!configured) {
-    SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
-    SX_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&global_select_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8));
-    configured = true;
-  }
   sx_prof_begin(SX_K_SELECT, st);
   if (per <= 64)
     global_select_kernel<true><<<1, kSelThreads, shmem, st>>>(score, idx, n, k, B, per, out_row, out_token,
@@ -618,4 +619,53 @@ extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_
   sx_prof_end(st);
   SX_LAUNCH_CHECK();
   return SX_OK;
+}
+
+}  // namespace
+
+extern "C" int sx_expand_topk(const float* logits, const float* cum_logp, int32_t N, int32_t V, int32_t k, int32_t B,
+                              int32_t* out_row, int32_t* out_token, float* out_cum_logp, int32_t* n_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!logits || !cum_logp || !out_row || !out_token || !out_cum_logp || !n_out) return SX_ERR_NULL;
+  if (!row_shape_ok(N, V, k) || B < 1 || B > 8192) return SX_ERR_SHAPE;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) ||
+      workspace_bytes < sx_expand_topk_workspace(N, V, k, B))
+    return SX_ERR_WORKSPACE;
+  const size_t nk = sx_align_up((size_t)N * (size_t)k * 4, 256);
+  char* ws = static_cast<char*>(workspace);
+  return expand_topk_run(logits, cum_logp, N, V, k, B, out_row, out_token, out_cum_logp, n_out,
+                         reinterpret_cast<float*>(ws + SX_WS_HEADER), reinterpret_cast<float*>(ws + SX_WS_HEADER + nk),
+                         reinterpret_cast<int*>(ws + SX_WS_HEADER + 2 * nk), (hipStream_t)stream);
+}
+
+// ---- the same step for callers that cannot allocate ----------------------------------------------------
+// The three candidate arrays (score, log-probability, token id; N*k entries each) live in a file-scope
+// device array instead of a caller's workspace.  Every GPU holds its own copy of the array at its own
+// address; the name below is only a host-side handle for hipGetSymbolAddress, never a kernel argument.
+namespace {
+constexpr int kStaticMaxCand = SX_EXPAND_STATIC_MAX_CANDIDATES;
+static __device__ __align__(256) unsigned char scratch[3 * (size_t)kStaticMaxCand * 4];
+void* g_scratch_ptr[64] = {};  // per device: address of that device's copy of `scratch`
+}  // namespace
+
+extern "C" int sx_expand_topk_static(const float* logits, const float* cum_logp, int32_t N, int32_t V, int32_t k,
+                                     int32_t B, int32_t* out_row, int32_t* out_token, float* out_cum_logp,
+                                     int32_t* n_out, void* stream) {
+  if (!logits || !cum_logp || !out_row || !out_token || !out_cum_logp || !n_out) return SX_ERR_NULL;
+  if (!row_shape_ok(N, V, k) || B < 1 || B > 8192) return SX_ERR_SHAPE;
+  if ((long long)N * k > kStaticMaxCand) return SX_ERR_SHAPE;  // beyond the fixed scratch: use sx_expand_topk
+  int dev = 0;
+  SX_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return SX_ERR_HIP;
+  if (!g_scratch_ptr[dev]) {  // first call on this device (with it current): look its copy of the array up
+    void* p = nullptr;
+    SX_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SX_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  char* base = static_cast<char*>(g_scratch_ptr[dev]);
+  const size_t nk = (size_t)kStaticMaxCand * 4;
+  return expand_topk_run(logits, cum_logp, N, V, k, B, out_row, out_token, out_cum_logp, n_out,
+                         reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + nk),
+                         reinterpret_cast<int*>(base + 2 * nk), (hipStream_t)stream);
 }

@@ -55,6 +55,8 @@ def test_host_side_errors_return_codes(sx):
     assert L.sx_expand_topk(one, one, 4, 100, 2, 4, one, one, one, one, None, 0, None) == -3
     assert L.sx_expand_topk(one, one, 4, 100, 2, 4, one, one, one, one, C.c_void_p(264), 1 << 20, None) == -3  # misaligned
     assert L.sx_expand_topk(one, one, 4, 100, 2, 4, one, one, one, one, one, 16, None) == -3
+    assert L.sx_expand_topk_static(one, one, 4097, 32000, 16, 64, one, one, one, one, None) == -2      # > 65536 candidates
+    assert L.sx_expand_topk_static(one, one, 4, 100, 2, 4, one, None, one, one, None) == -1
     assert L.sx_accept_walk(one, None, one, one, 4, 100, 0.6, 1.5, 1, 0, one, one, one, one, 1 << 20, None) == -2
     assert L.sx_accept_walk(one, None, one, one, 4, 1 << 20, 0.6, 0.9, 1, 0, one, one, one, one, 1 << 20, None) == -2
     assert L.sx_accept_walk(one, None, None, one, 4, 100, 0.6, 0.9, 1, 0, one, one, one, one, 1 << 20, None) == -1
