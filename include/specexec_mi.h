@@ -99,7 +99,9 @@ typedef struct sx_weights {
  *
  * Supported shapes.  SX_F32: head_dim even and <= 256, P + 2T <= 15360 (the scores of one node live in LDS).  SX_BF16: head_dim
  * == 128, n_q_heads/n_kv_heads in {1,2,4,8}, d_model, Hq*Dh and d_ffn multiples of 64.
- * T >= 1, P >= 0, T <= 16384.  In SX_BF16 the tensors a bf16 model materialises (normed
+ * T >= 1, P >= 0, T <= 16384.  The bf16 GEMM kernels address each operand with 32-bit byte offsets, so
+ * every matrix on its own must be smaller than 4 GiB: T*d_model*2, T*d_ffn*2, vocab*d_model*2 (embed is
+ * exempt), d_ffn*d_model*2 and Hq*Dh*d_model*2 bytes all < 2^32, else SX_ERR_SHAPE.  In SX_BF16 the tensors a bf16 model materialises (normed
  * activations, q, k, v, attention output, SwiGLU output) are rounded to bf16; the residual
  * stream, softmax and norm statistics, and all accumulation are fp32.
  * ---------------------------------------------------------------------------------------- */
@@ -124,7 +126,8 @@ int sx_verify_tree_cached(const sx_weights *w, const void *prefix_k, const void 
  * values, rows [first, T) are written.  They are required when first > 0.  tree_tokens and parent_idx
  * describe all T nodes (indices are global); logits_out is device float [T - first][V], row i for node
  * first + i.  Workspace as for sx_verify_tree(P, T).  sx_verify_tree_cached is this call with first = 0
- * and tree_capacity = T. */
+ * and tree_capacity = T.  Every call starts the workspace's status word afresh: check it after each
+ * call of a sequence that grows one tree. */
 int sx_verify_tree_range(const sx_weights *w, const void *prefix_k, const void *prefix_v,
                          int32_t capacity, int32_t P, const int32_t *tree_tokens,
                          const int32_t *parent_idx, int32_t T, int32_t first, float *logits_out,
@@ -243,8 +246,8 @@ int sx_specexec_round(const sx_weights *w, void *cache_k, void *cache_v, int32_t
  *                       children, node 0 = root with parent -1): the input sx_verify_tree expects.
  * Supported: D * B <= 16384, k <= 256 (k is clamped to the vocabulary), min(K, B k) <= 8192,
  * K + min(K, B k) <= 16384, and the model shapes of sx_verify_tree with T = D * B.
- * workspace: sx_draft_tree_workspace bytes, 256-byte aligned; sx_check_status on it reports the
- * status of the forward passes.
+ * workspace: sx_draft_tree_workspace bytes, 256-byte aligned; sx_check_status on it reports an error of
+ * any of the D forward passes (the first pass resets the status word, the later ones leave an error in place).
  * ---------------------------------------------------------------------------------------- */
 size_t sx_draft_tree_workspace(const sx_model_cfg *cfg, int32_t P, int32_t K, int32_t D, int32_t B,
                                int32_t k);
@@ -271,7 +274,7 @@ int sx_row_logsoftmax_topk(const float *logits, int32_t N, int32_t V, int32_t k,
 
 /* Y = X W^T with bf16 operands and fp32 accumulation on the matrix cores; the linear layers
  * of the decoder forward (Alg. 1, FORWARD).  X device bf16 [M][K] row-major, W device bf16
- * [N][K] row-major, K % 64 == 0.  mode 0: Y float [M][N] = acc;  mode 1: Y float [M][N] += acc
+ * [N][K] row-major, K % 64 == 0; M*K*2 and N*K*2 bytes each below 4 GiB (SX_ERR_SHAPE otherwise).  mode 0: Y float [M][N] = acc;  mode 1: Y float [M][N] += acc
  * (residual add);  mode 2: W2 is a second [N][K] matrix and Y bf16 [M][N] =
  * bf16(silu(X W^T) * (X W2^T)) (SwiGLU).  W2 is ignored in modes 0 and 1. */
 int sx_gemm_bf16(const void *X, const void *W, const void *W2, void *Y, int32_t M, int32_t N,

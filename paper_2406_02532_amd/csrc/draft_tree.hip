@@ -75,6 +75,9 @@ __global__ __launch_bounds__(kThreads) void draft_take_kernel(DraftBufs b, int c
   uint32_t* Hout = b.H[cur ^ 1];
   const int n = min(b.state->hn[cur], kSortCap);
   const float thr = b.state->thr;
+  // read here, ahead of every barrier: lane 0 overwrites the state at the end of the kernel, and a wave that
+  // read it only then could see the new value and take the other side of the (barrier-holding) branch below
+  const int alive_before = b.state->n_alive;
   const int np2 = next_pow2(n < 2 ? 2 : n);
   for (int i = tid; i < np2; i += kThreads) {
     unsigned long long k = ~0ull;
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void draft_take_kernel(DraftBufs b, int c
   }
   for (int i = pops + tid; i < heap; i += kThreads) Hout[i - pops] = (uint32_t)(keys[i] & 0xFFFFFFFFull);
   __syncthreads();  // the slots just written are read below
-  const int alive_now = b.state->n_alive + nb;
+  const int alive_now = alive_before + nb;
   float new_thr = thr;
   if (alive_now >= K) {  // T := K-th best cumulative log-probability in the tree
     const float* cum = b.cum;
@@ -316,8 +319,9 @@ extern "C" int sx_draft_tree(const sx_weights* w, const void* prefix_k, const vo
     draft_take_kernel<<<1, kThreads, 0, st>>>(L.b, cur, base, B, K);
     SX_LAUNCH_CHECK();
     cur ^= 1;
-    SX_TRY(sx_verify_tree_range(w, prefix_k, prefix_v, capacity, P, L.b.tok, L.b.par, base + B, base, L.logits, L.tree_k,
-                                L.tree_v, L.S, L.verify_ws, L.verify_ws_bytes, st));
+    // the first iteration resets the status word, the later ones keep what an earlier one recorded
+    SX_TRY(sx_verify_tree_range_impl(w, prefix_k, prefix_v, capacity, P, L.b.tok, L.b.par, base + B, base, L.logits,
+                                     L.tree_k, L.tree_v, L.S, L.verify_ws, L.verify_ws_bytes, d > 0, st));
     SX_TRY(sx_expand_topk(L.logits, L.b.cum + base, B, c.vocab, L.ksel, L.bsel, L.sel_row, L.sel_tok, L.sel_score,
                           L.sel_n, L.expand_ws, L.expand_ws_bytes, st));
     draft_merge_kernel<<<1, kThreads, 0, st>>>(L.b, cur, base, L.sel_row, L.sel_tok, L.sel_score, L.sel_n, L.logcap,

@@ -527,7 +527,10 @@ int launch(const GemmArgs& a, hipStream_t st) {
 
 int sx_launch_gemm_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                         void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
-  if (M < 1 || K < BK || K % BK != 0 || n0 < 1) return SX_ERR_SHAPE;
+  if (M < 1 || K < BK || K % BK != 0 || n0 < 1 || n1 < 0 || n2 < 0) return SX_ERR_SHAPE;
+  if (!sx_operand_fits_u32(M, 2ll * K) || !sx_operand_fits_u32(n0, 2ll * K) || !sx_operand_fits_u32(n1, 2ll * K) ||
+      !sx_operand_fits_u32(n2, 2ll * K))
+    return SX_ERR_SHAPE;
   if (M <= 128)  // weight-streaming regime: narrow tiles
     return sx_launch_gemm_skinny_bf16(X, W0, W1, W2, n0, n1, n2, Y, M, K, mode, split_ws, split_ws_bytes, st);
   // a 16-row copy group must not straddle two stacked weight matrices
@@ -569,6 +572,9 @@ int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, 
                                  const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
                                  size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || hq < 1 || hkv < 1) return SX_ERR_SHAPE;
+  if (!sx_operand_fits_u32(M, 2ll * K) || !sx_operand_fits_u32(128ll * hq, 2ll * K) ||
+      !sx_operand_fits_u32(128ll * hkv, 2ll * K))
+    return SX_ERR_SHAPE;
   GemmArgs a;
   a.X = static_cast<const unsigned short*>(X);
   a.W0 = static_cast<const unsigned short*>(Wq);

@@ -253,7 +253,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
 // M <= 128.  Arguments as sx_launch_gemm_bf16 (modes store, residual, SwiGLU).
 int sx_launch_gemm_skinny_bf16(const void* X, const void* W0, const void* W1, const void* W2, int n0, int n1, int n2,
                                void* Y, int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
-  if (M < 1 || M > BM || K < BK || K % BK != 0 || n0 < 1) return SX_ERR_SHAPE;
+  if (M < 1 || M > BM || K < BK || K % BK != 0 || n0 < 1 || n1 < 0 || n2 < 0) return SX_ERR_SHAPE;
+  if (!sx_operand_fits_u32(M, 2ll * K) || !sx_operand_fits_u32(n0, 2ll * K) || !sx_operand_fits_u32(n1, 2ll * K) ||
+      !sx_operand_fits_u32(n2, 2ll * K))
+    return SX_ERR_SHAPE;
   if (mode != SX_GEMM_SWIGLU && ((n1 > 0 && n0 % 8 != 0) || (n2 > 0 && n1 % 8 != 0))) return SX_ERR_SHAPE;
   SkinnyArgs a;
   a.X = static_cast<const unsigned short*>(X);

@@ -260,7 +260,7 @@ int sx_launch_gemm_skinny_w4(const void* X, const void* qweight, const void* sca
                              void* Y, int M, int N, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || M > BM || K < BK || K % BK != 0 || N < 1 || group < BK || (group & (group - 1)) != 0 || K % group != 0)
     return SX_ERR_SHAPE;
-  if ((unsigned long long)N * K / 2 >= (1ull << 32)) return SX_ERR_SHAPE;  // 32-bit byte offsets into qweight
+  if (!sx_operand_fits_u32(N, K / 2) || !sx_operand_fits_u32(M, 2ll * K)) return SX_ERR_SHAPE;  // 32-bit byte offsets
   if (mode != SX_GEMM_STORE && mode != SX_GEMM_RESIDUAL) return SX_ERR_SHAPE;
   W4Args a;
   a.X = static_cast<const unsigned short*>(X);

@@ -6,9 +6,11 @@
 // ---- tree bookkeeping (tree_prep.hip) -------------------------------------------------------------
 // Checks parent/token ranges (status word <- SX_ERR_TREE on violation), writes sanitised copies,
 // the depth of every node and the rotary table cs[T][Dh/2] = (cos, sin) of (P+depth)*base^(-2j/Dh).
+// reset_status: the status word starts at SX_OK (false: an error recorded by an earlier call on the same
+// workspace stays, so a forward that grows a tree call by call reports the first bad batch at the end).
 int sx_launch_tree_prep(const int32_t* tokens, const int32_t* parent, int T, int V, int P, int head_dim,
                         float rope_base, int32_t* tok_s, int32_t* par_s, int32_t* depth, float2* rope_cs,
-                        int32_t* status, hipStream_t st);
+                        int32_t* status, bool reset_status, hipStream_t st);
 // cs[T][head_dim/2] = (cos, sin) of (P + pos[i]) * base^(-2j/head_dim), evaluated in fp64.
 int sx_launch_rope_table(const int32_t* pos, int T, int P, int head_dim, float rope_base, float2* rope_cs, hipStream_t st);
 // Per query tile of `nodes_per_tile` consecutive nodes: the sorted union of their ancestors
@@ -35,6 +37,12 @@ int sx_launch_gemm_f32(const float* X, const float* W, float* Y, int M, int N, i
 int sx_launch_tree_attn_f32(const float* q, const float* k_tree, const float* v_tree, const float* k_prefix,
                             const float* v_prefix, const int32_t* par_s, const int32_t* depth, int T, int first, int P,
                             int Hq, int Hkv, int Dh, float* out, hipStream_t st);
+
+// The GEMM kernels address their operands with 32-bit byte offsets from the start of each matrix: every
+// operand (X, and each stacked weight matrix on its own) must stay below 4 GiB.
+static inline bool sx_operand_fits_u32(long long rows, long long row_bytes) {
+  return rows >= 0 && row_bytes >= 0 && (unsigned long long)rows * (unsigned long long)row_bytes < (1ull << 32);
+}
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------------
 enum { SX_GEMM_STORE = 0, SX_GEMM_RESIDUAL = 1, SX_GEMM_SWIGLU = 2, SX_GEMM_QKV_ROPE = 3 };
@@ -78,6 +86,14 @@ static inline int sx_attn_nodes_per_tile(int Hq, int Hkv, int Tq) {
   while (npt > lo && ((Tq + npt - 1) / npt) * Hkv < 256) npt /= 2;
   return npt;
 }
+
+// ---- the forward itself (verify_tree.hip) -----------------------------------------------------------------
+// sx_verify_tree_range with one more knob: keep_status leaves an error that an earlier call recorded in the
+// workspace's status word in place (the draft loop's later iterations), instead of starting from SX_OK.
+int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t capacity,
+                              int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T, int32_t first,
+                              float* logits_out, void* tree_k_out, void* tree_v_out, int32_t tree_capacity,
+                              void* workspace, size_t workspace_bytes, bool keep_status, void* stream);
 
 // ---- optional event timing around single launches (prof.hip) -----------------------------------------
 enum {

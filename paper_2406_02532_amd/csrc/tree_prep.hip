@@ -13,7 +13,7 @@ constexpr int kPrepThreads = 1024;
 __global__ __launch_bounds__(kPrepThreads) void tree_prep_kernel(const int* __restrict__ tokens,
                                                                  const int* __restrict__ parent, int T, int V,
                                                                  int* __restrict__ tok_s, int* __restrict__ par_s,
-                                                                 int* __restrict__ depth, int* __restrict__ status) {
+                                                                 int* __restrict__ depth, int* __restrict__ status, int reset) {
   extern __shared__ int sp[];
   const int tid = threadIdx.x;
   int bad = 0;
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kPrepThreads) void tree_prep_kernel(const int* __re
     par_s[i] = p;
     tok_s[i] = t;
   }
-  if (tid == 0) status[0] = SX_OK;
+  if (tid == 0 && reset) status[0] = SX_OK;  // a call that continues a tree (reset == 0) keeps an earlier call's error
   __syncthreads();
   if (bad) status[0] = SX_ERR_TREE;
   for (int i = tid; i < T; i += kPrepThreads) {
@@ -108,8 +108,9 @@ __global__ __launch_bounds__(kQtThreads) void qtile_prep_kernel(const int* __res
 
 int sx_launch_tree_prep(const int32_t* tokens, const int32_t* parent, int T, int V, int P, int head_dim,
                         float rope_base, int32_t* tok_s, int32_t* par_s, int32_t* depth, float2* rope_cs,
-                        int32_t* status, hipStream_t st) {
-  tree_prep_kernel<<<1, kPrepThreads, (size_t)T * sizeof(int), st>>>(tokens, parent, T, V, tok_s, par_s, depth, status);
+                        int32_t* status, bool reset_status, hipStream_t st) {
+  tree_prep_kernel<<<1, kPrepThreads, (size_t)T * sizeof(int), st>>>(tokens, parent, T, V, tok_s, par_s, depth, status,
+                                                                     reset_status ? 1 : 0);
   SX_LAUNCH_CHECK();
   return sx_launch_rope_table(depth, T, P, head_dim, rope_base, rope_cs, st);
 }

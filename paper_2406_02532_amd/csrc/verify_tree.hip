@@ -114,6 +114,14 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
                                     int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T,
                                     int32_t first, float* logits_out, void* tree_k_out, void* tree_v_out,
                                     int32_t tree_capacity, void* workspace, size_t workspace_bytes, void* stream) {
+  return sx_verify_tree_range_impl(w, prefix_k, prefix_v, capacity, P, tree_tokens, parent_idx, T, first, logits_out,
+                                   tree_k_out, tree_v_out, tree_capacity, workspace, workspace_bytes, false, stream);
+}
+
+int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t capacity,
+                              int32_t P, const int32_t* tree_tokens, const int32_t* parent_idx, int32_t T, int32_t first,
+                              float* logits_out, void* tree_k_out, void* tree_v_out, int32_t tree_capacity,
+                              void* workspace, size_t workspace_bytes, bool keep_status, void* stream) {
   if (capacity < P || first < 0 || first >= T || tree_capacity < T) return SX_ERR_SHAPE;
   if (first > 0 && (!tree_k_out || !tree_v_out)) return SX_ERR_NULL;  // the earlier nodes' K/V live there
   const int n = T - first;  // rows of this call: nodes first .. T-1
@@ -140,7 +148,7 @@ extern "C" int sx_verify_tree_range(const sx_weights* w, const void* prefix_k, c
   int32_t* status = static_cast<int32_t*>(workspace);
 
   SX_TIMED(SX_K_PREP, sx_launch_tree_prep(tree_tokens, parent_idx, T, V, P, Dh, c.rope_base, L.tok_s, L.par_s, L.depth,
-                                          L.rope_cs, status, st));
+                                          L.rope_cs, status, !keep_status, st));
   if (bf)
     SX_TIMED(SX_K_PREP, sx_launch_qtile_prep(L.par_s, T, sx_attn_nodes_per_tile(Hq, Hkv, n), first, L.klist, L.kcnt,
                                              L.rowmask, st));
@@ -325,7 +333,7 @@ extern "C" int sx_tree_attention_bf16(const void* q, const void* k_tree, const v
   if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   SX_TRY(sx_launch_tree_prep(nullptr, parent_idx, T, 1, P, 128, 10000.f, L.tok_s, L.par_s, L.depth, L.cs,
-                             static_cast<int32_t*>(workspace), st));
+                             static_cast<int32_t*>(workspace), true, st));
   SX_TRY(sx_launch_qtile_prep(L.par_s, T, npt, 0, L.klist, L.kcnt, L.rowmask, st));
   return sx_launch_tree_attn_bf16(q, k_tree, v_tree, k_prefix, v_prefix, L.klist, L.kcnt, L.rowmask, T, T, P, n_q_heads,
                                   n_kv_heads, out, nullptr, 0, st);

@@ -62,5 +62,8 @@ def test_host_side_errors_return_codes(sx):
     assert L.sx_accept_walk(one, None, None, one, 4, 100, 0.6, 0.9, 1, 0, one, one, one, one, 1 << 20, None) == -1
     assert L.sx_gemm_bf16(one, one, None, one, 8, 8, 100, 0, None) == -2          # K % 64 != 0
     assert L.sx_gemm_bf16(one, one, None, one, 8, 8, 128, 2, None) == -1          # SwiGLU needs W2
+    assert L.sx_gemm_bf16(one, one, None, one, 256, 262144, 8192, 0, None) == -2  # W of 4 GiB: 32-bit offsets would wrap
+    assert L.sx_gemm_bf16(one, one, None, one, 64, 262144, 8192, 0, None) == -2   # the same through the narrow-tile kernel
+    assert L.sx_gemm_bf16(one, one, None, one, 65536, 64, 32768, 1, None) == -2   # X of 4 GiB
     assert L.sx_verify_tree(None, None, None, 0, one, one, 4, one, None, None, one, 1 << 20, None) == -1
     assert L.sx_row_logsoftmax_topk(one, 4, 100, 300, one, one, None) == -2
