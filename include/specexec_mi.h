@@ -148,8 +148,18 @@ int sx_verify_tree_range(const sx_weights *w, const void *prefix_k, const void *
  * sequential decoding would use (Sect. 4.1, seed-exact equivalence).
  *
  *   logits        device float [T][V]
- *   draft_probs   ignored (may be NULL): SpecExec accepts with the target probability alone;
- *                 only a SpecInfer-style ratio test would read it.
+ *   draft_probs   NULL: the walk above (SpecExec accepts with the target probability alone).
+ *                 Not NULL: device float [T][V], row i = the distribution the children of node i were
+ *                 drawn from (independent draws; equal tokens may be separate children).  The call then
+ *                 runs the comparison system of Sect. 4.1, speculative decoding's acceptance with
+ *                 probability P_target(x) / P_draft(x) capped at one, over the tree: with p the warped
+ *                 target distribution of the current node (nucleus renormalised) and q its draft row,
+ *                 the children are tried in index order, the j-th accepted when r_j q[x] < p[x]; a
+ *                 rejection replaces p by the renormalised positive part of p - q; after the last
+ *                 rejection the token is drawn from what p has become (inverse CDF in id order) and the
+ *                 walk ends.  r_j = u(seed + (j+1)*0xD6E8FEB86659FD93, position): one uniform per
+ *                 decision.  The emitted tokens follow the target's warped distribution; they are not
+ *                 seed-for-seed those of sequential sampling (the paper says as much of this baseline).
  *   path_out      device int32 [T]: visited nodes, path_out[0] == 0
  *   tokens_out    device int32 [T]: tokens_out[s] = token sampled at path_out[s]
  *   n_out         device int32 [1]: number of entries written to both (>= 1); the number of

@@ -16,6 +16,8 @@ from .model import (  # noqa: F401
 )
 from .generate import specexec_generate  # noqa: F401
 from .draft import create_draft_tree  # noqa: F401
-from .sampling import uniform01, sample_token, accept_walk, sequential_sample  # noqa: F401
+from .sampling import (  # noqa: F401
+    uniform01, sample_token, accept_walk, sequential_sample, warped_distribution, trial_uniform, specinfer_walk,
+)
 from .quant import unpack_w4, dequantize_w4, gemm_w4a16  # noqa: F401
 from .expand import log_softmax, row_topk, expand_topk  # noqa: F401

@@ -107,3 +107,90 @@ def sequential_sample(cfg, w, prefix_k, prefix_v, first_token, n_tokens, tempera
         out.append(x)
         seq.append(x)
     return out
+
+
+# ------------------------------------------------------------------------------------------
+# The comparison system of Sect. 4.1 ("Comparison to speculative decoding"): acceptance with
+# probability P_target / P_draft instead of P_target.
+# ------------------------------------------------------------------------------------------
+
+
+def warped_distribution(logits, temperature: float, top_p: float) -> np.ndarray:
+    """The distribution ``sample_token`` draws from, written out: softmax(logits / t) cut to its
+    nucleus and renormalised (t == 0: all mass on the lowest-id argmax)."""
+    x = np.asarray(logits, dtype=np.float64)
+    V = len(x)
+    p = np.zeros(V)
+    if temperature == 0.0:
+        p[int(np.argmax(x))] = 1.0
+        return p
+    z = x / temperature
+    e = np.exp(z - z.max())
+    e /= e.sum()
+    order = np.argsort(-e, kind="stable")
+    csum = np.cumsum(e[order])
+    n_keep = min(int(np.searchsorted(csum, top_p, side="left")) + 1, V)
+    p[order[:n_keep]] = e[order[:n_keep]]
+    return p / p.sum()
+
+
+def trial_uniform(seed: int, position: int, trial: int) -> float:
+    """The uniform of the ``trial``-th decision taken at one position (this mode needs several per
+    position): ``uniform01`` with the seed advanced by (trial + 1) * 0xD6E8FEB86659FD93 (mod 2^64)."""
+    return uniform01((int(seed) + (int(trial) + 1) * 0xD6E8FEB86659FD93) & _U64, position)
+
+
+def specinfer_walk(logits, draft_probs, tokens, parent, temperature, top_p, seed, pos0):
+    """Tree acceptance the way speculative decoding does it (Sect. 4.1: a drafted token x is accepted
+    with probability P_target(x) / P_draft(x), capped at one), for a tree whose children were *sampled*
+    from the draft distribution -- the baseline the paper compares with, multi-step speculative sampling
+    over a token tree.
+
+    At the current node, p is the warped target distribution of its row and q = draft_probs[cur] the
+    distribution its children were drawn from (independently; equal tokens may appear as separate
+    children).  The children are tried in index order: child c with token x is accepted when
+    r * q[x] < p[x], r = trial_uniform(seed, position, j) for the j-th child; the walk then moves to c.
+    A rejection replaces p by the renormalised positive part of p - q (the part of the target's mass
+    the draft did not cover) and goes on to the next child.  When every child is rejected (or there is
+    none) the token is drawn from what p has become -- inverse CDF in id order at r * sum(p), r the
+    next uniform of the position -- and the walk ends.  The emitted tokens then follow the target's
+    warped distribution exactly, although no step samples from it directly.
+
+    Returns dict(path, tokens, margins): as ``accept_walk``; margins[i] = how far each decision taken at
+    step i was from flipping ('m_acc': min |r q[x] - p[x]| over the trials, 'm_u': distance of the
+    final draw to the nearest CDF edge, inf when the step ended in an acceptance)."""
+    tokens = np.asarray(tokens)
+    parent = np.asarray(parent)
+    depth = tree_depths(parent)
+    if parent[0] != -1:
+        raise ValueError("node 0 must be the root")
+    cur, path, out, margins = 0, [0], [], []
+    while True:
+        pos = pos0 + int(depth[cur]) + 1
+        p = warped_distribution(logits[cur], temperature, top_p)
+        q = np.asarray(draft_probs[cur], dtype=np.float64)
+        kids = np.nonzero(parent == cur)[0]
+        m_acc, nxt = np.inf, None
+        for j, c in enumerate(kids):
+            x = int(tokens[c])
+            r = trial_uniform(seed, pos, j)
+            m_acc = min(m_acc, abs(r * q[x] - p[x]))
+            if r * q[x] < p[x]:
+                nxt = int(c)
+                break
+            rest = np.maximum(p - q, 0.0)
+            if rest.sum() > 0.0:          # (zero only when p <= q everywhere, i.e. p == q: then x was accepted)
+                p = rest / rest.sum()
+        if nxt is not None:
+            out.append(int(tokens[nxt]))
+            margins.append(dict(m_acc=float(m_acc), m_u=np.inf))
+            cur = nxt
+            path.append(cur)
+            continue
+        target = trial_uniform(seed, pos, len(kids)) * p.sum()
+        cdf = np.cumsum(p)
+        hit = np.nonzero((p > 0) & (cdf > target))[0]
+        x = int(hit[0]) if len(hit) else int(np.nonzero(p > 0)[0][-1])
+        out.append(x)
+        margins.append(dict(m_acc=float(m_acc), m_u=float(np.min(np.abs(cdf[p > 0] - target)))))
+        return dict(path=path, tokens=out, margins=margins)

@@ -144,3 +144,97 @@ def test_plain_categorical_frequencies(sx):
     cnt = np.bincount(torch.stack([o[0] for o in outs]).cpu().numpy(), minlength=6)
     chi2 = ((cnt - n * p) ** 2 / (n * p)).sum()
     assert chi2 < 25.7
+
+
+# ------------------------------------------------------------------------------------------------
+# acceptance by the ratio of target and draft probability (Sect. 4.1, "Comparison to speculative
+# decoding"): sx_accept_walk with draft_probs against oracle.specinfer_walk
+# ------------------------------------------------------------------------------------------------
+
+def _sampled_tree(T, V, n_children, seed):
+    """A tree whose children were drawn from a draft distribution, with that distribution per node and target
+    logits that agree with it only roughly: draft rows = softmax of N(0,1) noise with a few lifted tokens; every
+    node (breadth first, until T nodes) draws n_children tokens independently from its row (equal draws stay
+    separate children); target logits = draft logits + N(0, 1.5) noise."""
+    r = np.random.default_rng(seed)
+    tokens, parent, rows = [int(r.integers(V))], [-1], []
+    i = 0
+    while i < len(tokens):
+        lg = r.standard_normal(V)
+        lift = r.choice(V, size=min(5, V), replace=False)
+        lg[lift] += np.log(V) + r.uniform(2.0, 6.0, size=len(lift))   # the lifted tokens hold most of the mass at any V
+        q = np.exp(lg - lg.max())
+        q /= q.sum()
+        rows.append((lg, q))
+        if len(tokens) < T:
+            for x in r.choice(V, size=min(n_children, T - len(tokens)), p=q):
+                tokens.append(int(x))
+                parent.append(i)
+        i += 1
+    draft_probs = np.stack([q for _, q in rows]).astype(np.float32)
+    target = np.stack([lg for lg, _ in rows]) + 1.5 * r.standard_normal((len(rows), V))
+    return np.array(tokens, np.int32), np.array(parent, np.int32), target.astype(np.float32), draft_probs
+
+
+SI_MARGIN = 1e-5   # probabilities are at most one and carry ~1e-6 of absolute fp32 error
+
+
+def _si_safe(ref):
+    return all(min(m["m_acc"], m["m_u"]) > SI_MARGIN for m in ref["margins"])
+
+
+@pytest.mark.parametrize("V,T,kids", [(1000, 40, 3), (32000, 60, 4), (50000, 24, 2), (64, 30, 3)])
+@pytest.mark.parametrize("t,top_p", [(0.6, 0.9), (1.0, 1.0), (0.0, 1.0)])
+def test_ratio_acceptance_matches_oracle(sx, V, T, kids, t, top_p):
+    tok, par, target, dq = _sampled_tree(T, V, kids, seed=V + T)
+    ld, qd, td, pd = to_dev(target), to_dev(dq), to_dev(tok), to_dev(par)
+    checked = accepted = 0
+    for seed in range(24):
+        ref = oracle.specinfer_walk(target, dq, tok, par, t, top_p, seed=seed, pos0=31)
+        if not _si_safe(ref):
+            continue
+        path, toks, n, ws = sx.accept_walk(ld, td, pd, t, top_p, seed, 31, draft_probs=qd)
+        torch.cuda.synchronize()
+        n = int(n.item())
+        assert sx.check_status(ws) == 0
+        assert path[:n].cpu().tolist() == ref["path"], (seed, ref)
+        assert toks[:n].cpu().tolist() == ref["tokens"]
+        checked += 1
+        accepted += len(ref["path"]) - 1
+    assert checked >= 12 and accepted >= 4        # the walks do go down the tree: target and draft agree roughly
+
+
+def test_ratio_acceptance_emits_the_target_distribution(sx):
+    """chi-square on the device: k children drawn from q by numpy; the first emitted token must follow p."""
+    p = np.array([0.02, 0.4, 0.08, 0.25, 0.05, 0.2])
+    q = np.array([0.3, 0.1, 0.25, 0.05, 0.2, 0.1])
+    k, n = 3, 4000
+    r = np.random.default_rng(5)
+    ld = to_dev(np.tile(np.log(p).astype(np.float32), (k + 1, 1)))
+    qd = to_dev(np.tile(q.astype(np.float32), (k + 1, 1)))
+    pd = to_dev(np.array([-1] + [0] * k, np.int32))
+    outs = []
+    for seed in range(n):
+        td = to_dev(np.array([0] + list(r.choice(6, size=k, p=q)), np.int32))
+        outs.append(sx.accept_walk(ld, td, pd, 1.0, 1.0, seed, 5, draft_probs=qd)[1])
+    torch.cuda.synchronize()
+    cnt = np.bincount(torch.stack([o[0] for o in outs]).cpu().numpy(), minlength=6)
+    chi2 = ((cnt - n * p) ** 2 / (n * p)).sum()
+    assert chi2 < 25.7, (chi2, cnt / n)
+
+
+def test_ratio_acceptance_special_cases(sx):
+    p = np.array([0.02, 0.4, 0.08, 0.25, 0.05, 0.2])
+    # draft == target: every first child is accepted, down the chain; then one token past the leaf
+    tok, par = np.array([3, 1, 4, 1], np.int32), np.array([-1, 0, 1, 2], np.int32)
+    rows = np.tile(np.log(p).astype(np.float32), (4, 1))
+    for seed in range(8):
+        path, toks, n, _ = sx.accept_walk(to_dev(rows), to_dev(tok), to_dev(par), 1.0, 1.0, seed, 2,
+                                          draft_probs=to_dev(np.tile(p.astype(np.float32), (4, 1))))
+        torch.cuda.synchronize()
+        assert int(n.item()) == 4 and path[:4].cpu().tolist() == [0, 1, 2, 3] and toks[:3].cpu().tolist() == [1, 4, 1]
+    # a child token outside the vocabulary is reported, not indexed
+    bad = np.array([3, 99], np.int32)
+    _, _, _, ws = sx.accept_walk(to_dev(rows[:2]), to_dev(bad), to_dev(np.array([-1, 0], np.int32)), 1.0, 1.0, 0, 0,
+                                 draft_probs=to_dev(np.tile(p.astype(np.float32), (2, 1))))
+    assert sx.check_status(ws) == -6

@@ -175,3 +175,121 @@ def test_generation_over_many_rounds_equals_sequential_sampling(model):
 
     out, per_round = oracle.specexec_generate(cfg, w, prompt, 3, informed, 0.6, 0.9, seed=3)
     assert out == truth[:len(out)] and all(n >= 3 for n in per_round)
+
+
+# ------------------------------------------------------------------------------------------------
+# specinfer_walk: acceptance with probability P_target / P_draft (Sect. 4.1, "Comparison to
+# speculative decoding").  What fixes it: the emitted tokens must follow the target's (warped)
+# distribution whatever the draft distribution is, and a single drafted token is accepted with
+# probability sum_x min(p(x), q(x)) (the closed form of speculative sampling).
+# ------------------------------------------------------------------------------------------------
+
+_P6 = np.array([0.02, 0.4, 0.08, 0.25, 0.05, 0.2])
+_Q6 = np.array([0.3, 0.1, 0.25, 0.05, 0.2, 0.1])
+
+
+def _star_tree(child_tokens):
+    """Root (token 0) with the given children."""
+    tokens = np.array([0] + list(child_tokens), dtype=np.int32)
+    parent = np.array([-1] + [0] * len(child_tokens), dtype=np.int32)
+    return tokens, parent
+
+
+def _rows(n, row):
+    return np.tile(np.asarray(row, dtype=np.float64), (n, 1))
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_specinfer_first_token_follows_the_target_distribution(k):
+    """k children drawn independently from q by the test's own generator (equal tokens stay separate
+    children); the first emitted token must be distributed as p.  chi-square, 5 dof."""
+    r = np.random.default_rng(100 + k)
+    n, cnt, accepted = 40000, np.zeros(6), 0
+    for s in range(n):
+        kids = r.choice(6, size=k, p=_Q6)
+        tokens, parent = _star_tree(kids)
+        w = oracle.specinfer_walk(_rows(k + 1, np.log(_P6)), _rows(k + 1, _Q6), tokens, parent, 1.0, 1.0, seed=s, pos0=5)
+        cnt[w["tokens"][0]] += 1
+        accepted += len(w["path"]) > 1
+        assert len(w["tokens"]) == len(w["path"]) and all(tokens[c] == t for c, t in zip(w["path"][1:], w["tokens"]))
+    chi2 = ((cnt - n * _P6) ** 2 / (n * _P6)).sum()
+    assert chi2 < 25.7, (chi2, cnt / n)      # p ~ 1e-4
+    if k == 1:   # one drafted token is accepted with probability sum min(p, q) = 0.47
+        exp = np.minimum(_P6, _Q6).sum()
+        assert abs(accepted / n - exp) < 4 * np.sqrt(exp * (1 - exp) / n), (accepted / n, exp)
+
+
+def test_specinfer_warped_target_and_plain_sampling_agree_in_distribution():
+    """With temperature and nucleus the target is the warped distribution; the draft one is used as given."""
+    logits = np.log(_P6)
+    p = oracle.warped_distribution(logits, 0.7, 0.9)
+    assert abs(p.sum() - 1) < 1e-12 and (p == 0).sum() >= 1          # the nucleus drops the tail
+    # the very distribution sample_token draws from: frequencies over a fine grid of uniforms
+    grid = (np.arange(20000) + 0.5) / 20000
+    freq = np.bincount([oracle.sample_token(logits, 0.7, 0.9, u)[0] for u in grid], minlength=6) / len(grid)
+    assert np.abs(freq - p).max() < 1e-4
+    r = np.random.default_rng(7)
+    n, cnt = 40000, np.zeros(6)
+    for s in range(n):
+        tokens, parent = _star_tree(r.choice(6, size=2, p=_Q6))
+        w = oracle.specinfer_walk(_rows(3, logits), _rows(3, _Q6), tokens, parent, 0.7, 0.9, seed=s, pos0=0)
+        cnt[w["tokens"][0]] += 1
+    keep = p > 0
+    assert cnt[~keep].sum() == 0
+    chi2 = ((cnt[keep] - n * p[keep]) ** 2 / (n * p[keep])).sum()
+    assert chi2 < 27.9, (chi2, cnt / n, p)
+
+
+def test_specinfer_two_levels_joint_distribution():
+    """Depth 2: the pair of the first two emitted tokens must follow p1(x1) * p2(x2 | node of x1) -- the walk has
+    to move to the accepted child and use that child's rows.  A second token exists only after an acceptance, so
+    the comparison is made on the joint counts of accepted-first-token x second token, against p1-mass accepted."""
+    V = 4
+    p1, q1 = np.array([0.1, 0.2, 0.3, 0.4]), np.array([0.4, 0.3, 0.2, 0.1])
+    p2 = [np.array([0.7, 0.1, 0.1, 0.1]), np.array([0.1, 0.7, 0.1, 0.1]), np.array([0.25, 0.25, 0.25, 0.25]),
+          np.array([0.05, 0.05, 0.1, 0.8])]
+    q2 = np.array([0.25, 0.25, 0.25, 0.25])
+    r = np.random.default_rng(3)
+    n = 60000
+    second = np.zeros((V, V))
+    first = np.zeros(V)
+    for s in range(n):
+        k1 = r.choice(V, size=2, p=q1)
+        tokens, parent = [0], [-1]
+        for t in k1:
+            tokens.append(int(t)); parent.append(0)
+        for ci in (1, 2):                                  # each first-level child gets one child drawn from q2
+            tokens.append(int(r.choice(V, p=q2))); parent.append(ci)
+        tokens, parent = np.array(tokens, dtype=np.int32), np.array(parent, dtype=np.int32)
+        logits = np.stack([np.log(p1)] + [np.log(p2[t]) for t in tokens[1:3]] + [np.log(q2)] * 2)
+        dq = np.stack([q1, q2, q2, q2, q2])
+        w = oracle.specinfer_walk(logits, dq, tokens, parent, 1.0, 1.0, seed=s, pos0=9)
+        first[w["tokens"][0]] += 1
+        if len(w["path"]) > 1:
+            second[w["tokens"][0], w["tokens"][1]] += 1
+    assert ((first - n * p1) ** 2 / (n * p1)).sum() < 21.1            # 3 dof
+    for a in range(V):                                                 # given the first token was an accepted a
+        na = second[a].sum()
+        assert na > 2000
+        assert ((second[a] - na * p2[a]) ** 2 / (na * p2[a])).sum() < 21.1, (a, second[a] / na)
+
+
+def test_specinfer_special_cases():
+    # draft == target: the first child is always accepted (ratio one), down a whole chain
+    tokens, parent = np.array([3, 1, 4, 1], dtype=np.int32), np.array([-1, 0, 1, 2], dtype=np.int32)
+    for s in range(50):
+        w = oracle.specinfer_walk(_rows(4, np.log(_P6)), _rows(4, _P6), tokens, parent, 1.0, 1.0, seed=s, pos0=2)
+        assert w["path"] == [0, 1, 2, 3] and w["tokens"][:3] == [1, 4, 1] and len(w["tokens"]) == 4
+    # a child whose token the target gives no mass is never accepted; greedy target: only the argmax is
+    p = np.array([0.0, 0.5, 0.5, 0.0, 0.0, 0.0])
+    with np.errstate(divide="ignore"):
+        lg = np.log(p)
+    tokens, parent = _star_tree([0, 3, 2])
+    for s in range(200):
+        w = oracle.specinfer_walk(_rows(4, lg), _rows(4, _Q6), tokens, parent, 1.0, 1.0, seed=s, pos0=0)
+        assert w["tokens"][0] in (1, 2) and (len(w["path"]) == 1 or w["path"][1] == 3)
+        g = oracle.specinfer_walk(_rows(4, np.log(_P6)), _rows(4, _Q6), *_star_tree([0, 1, 3]), 0.0, 1.0, seed=s, pos0=0)
+        assert g["tokens"][0] == 1 and g["path"][:2] == [0, 2]
+    # uniforms: a new one for every trial of a position, none shared with the plain walk's
+    us = {oracle.trial_uniform(5, 10, j) for j in range(8)} | {oracle.uniform01(5, 10)}
+    assert len(us) == 9
