@@ -26,15 +26,38 @@ CAL_COPY_BYTES = 1 << 30
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_gateup_swiglu_c5_hbm_traffic.txt")
 
 
+KERNEL_SOURCES = {"gemm": os.path.join(ROOT, "paper_2406_02532_amd", "csrc", "gemm_bf16.hip"),
+                  "attn": os.path.join(ROOT, "paper_2406_02532_amd", "csrc", "tree_attn_bf16.hip")}
+# What the chip sustains, measured on the box with kernels that do nothing else (pure register loop of
+# v_mfma_f32_16x16x32_bf16 on real operand data: the matrix pipe is power-limited; a plain streaming read of
+# 262 MB): the second denominator beside the vendor's peak.
+MEASURED_PEAK_BF16_TFLOPS = 1950.0
+MEASURED_PEAK_HBM_READ_GBPS = 6200.0
+
+
+def source_sha256(which):
+    import hashlib
+    return hashlib.sha256(open(KERNEL_SOURCES[which], "rb").read()).hexdigest()
+
+
 def measured_traffic():
-    """bytes per launch recorded in TRAFFIC_FILE ('traffic_bytes_per_launch = N'), or None."""
+    """Counter figures recorded in TRAFFIC_FILE ('name = value' lines), each valid only while the kernel source
+    it was measured on is unchanged: the file stores the sha256 of that source, and a figure whose source has
+    changed since is reported as None (re-measure with the two commands the file states)."""
+    vals = {}
     try:
         for line in open(TRAFFIC_FILE):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1].split()[0])
+            if " = " in line and not line.startswith(" "):
+                k, v = line.split(" = ", 1)
+                vals[k.strip()] = v.split()[0]
     except OSError:
-        pass
-    return None
+        return {}
+    out = {}
+    if vals.get("gemm_source_sha256") == source_sha256("gemm") and "traffic_bytes_per_launch" in vals:
+        out["gemm_gateup"] = float(vals["traffic_bytes_per_launch"])
+    if vals.get("attn_source_sha256") == source_sha256("attn") and "attn_fetch_bytes_per_launch" in vals:
+        out["attn_fetch"] = float(vals["attn_fetch_bytes_per_launch"])
+    return out
 
 
 def log(*a):
@@ -145,6 +168,12 @@ def main():
     torch.cuda.synchronize()
     sx.profile_disable()
     records = sx.profile_read(launches_per_step + 64)
+    # ---------------- a walk that really walks (untimed by the headline) ------------------------------------
+    # On a random-init target the walk leaves the tree at once.  Crafted logits (noise plus a large boost on the
+    # token of the next node along the path to the deepest leaf) make accept_walk take one step per tree level
+    # and commit_kv copy that many rows in every layer; both are timed with HIP events.
+    walk = walk_block(sx, wl, torch, np, dev, cfg, tok, par, tok_d, par_d, pk, pv, tree_k, tree_v, P, temperature, top_p)
+    sweep = t_sweep(sx, wl, torch, np, dev, cfg, mw, pk, pv, P, k_tree, T) if args.workload == "C5" else None
     if args.calibration_copy:
         src = torch.full((CAL_COPY_BYTES // 4,), 1.0, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -188,21 +217,39 @@ def main():
         kernels[name] = {k: round(v, 6) for k, v in e.items()}
     total_flop = cfg.n_layers * (flops["gemm_qkv"] + flops["gemm_o"] + flops["gemm_gateup_swiglu"] + flops["gemm_down"]
                                  + flops["tree_attn"]) + flops["gemm_lmhead"]
+    traffic = measured_traffic() if args.workload == "C5" else {}
     roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<2, true> (gate|up GEMM + SwiGLU, M=%d N=%d K=%d)" % (T, 2 * F, d),
                     achieved=round(kernels[dom]["tflops"], 3), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 5),
-                    traffic=measured_traffic() if args.workload == "C5" else None,
+                    traffic=traffic.get("gemm_gateup"),
                     algorithmic_bytes_per_launch=2.0 * (T * d + 2 * F * d + T * F),
                     flop_per_launch=flops[dom], ms_avg=kernels[dom]["ms_avg"],
                     note="peak is the nominal dense bf16 figure; with real operand data the matrix pipe is power-limited: "
                          "a pure register loop of v_mfma_f32_16x16x32_bf16 sustains 1.93-1.97 PFLOP/s on this chip")
+    roofline["frac_of_measured_peak"] = round(kernels[dom]["tflops"] / MEASURED_PEAK_BF16_TFLOPS, 5)
+    roofline["measured_peak"] = MEASURED_PEAK_BF16_TFLOPS
     other = []
+    for name, label in (("gemm_qkv", "gemm_bf16_kernel<3> (QKV + rotary)"), ("gemm_o", "gemm_bf16_kernel<1> (O + residual)"),
+                        ("gemm_down", "gemm_bf16_kernel<1> (down + residual)"), ("tree_attn", "tree_attn_bf16_kernel")):
+        if name in kernels:
+            other.append(dict(kernel=label, bound="mfma", achieved=kernels[name]["tflops"], peak=PEAK_BF16_TFLOPS,
+                              unit="TFLOP/s", frac=kernels[name]["frac_mfma_peak"],
+                              frac_of_measured_peak=round(kernels[name]["tflops"] / MEASURED_PEAK_BF16_TFLOPS, 5)))
+    kv_read_gbps = None
     if "tree_attn" in kernels:
-        other.append(dict(kernel="tree_attn_bf16_kernel", bound="mfma", achieved=kernels["tree_attn"]["tflops"],
-                          peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=kernels["tree_attn"]["frac_mfma_peak"]))
+        # K and V the attention has to read at least once per launch: prefix and tree rows of one layer
+        kv_bytes = 2.0 * (P + T) * Nkv * 2
+        kv_read_gbps = dict(algorithmic=round(kv_bytes / (kernels["tree_attn"]["ms_avg"] * 1e-3) / 1e9, 2),
+                            algorithmic_bytes_per_launch=kv_bytes,
+                            counter=(round(traffic["attn_fetch"] / (kernels["tree_attn"]["ms_avg"] * 1e-3) / 1e9, 2)
+                                     if "attn_fetch" in traffic else None),
+                            note="the kernel is bound by the matrix pipe, not by these reads: 16.8 MB per launch come from "
+                                 "HBM once and are re-read by the query tiles from L2; 'counter' = FETCH_SIZE of the launch "
+                                 "(q and K/V together) over its duration")
     if "row_topk" in kernels:
         other.append(dict(kernel="row_topk_kernel", bound="hbm", achieved=kernels["row_topk"]["gbps"], peak=PEAK_HBM_GBPS,
-                          unit="GB/s", frac=kernels["row_topk"]["frac_hbm_peak"]))
+                          unit="GB/s", frac=kernels["row_topk"]["frac_hbm_peak"],
+                          frac_of_measured_peak=round(kernels["row_topk"]["gbps"] / MEASURED_PEAK_HBM_READ_GBPS, 5)))
 
     out = dict(metric="verified tree tokens/s per target forward (T=%d)" % T, value=round(value, 2), unit="tokens/s",
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True,
@@ -217,13 +264,85 @@ def main():
                tflops=round(total_flop / (elapsed / args.steps) / 1e12, 2),
                frac_mfma_peak=round(total_flop / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 5),
                topk_hbm_gbps=kernels.get("row_topk", {}).get("gbps"),
-               accepted_tokens_last_step=int(n_o.item()),
+               kv_read_gbps=kv_read_gbps,
+               measured_peaks=dict(mfma_bf16_tflops=MEASURED_PEAK_BF16_TFLOPS, hbm_read_gbps=MEASURED_PEAK_HBM_READ_GBPS,
+                                   note="sustained on this chip by kernels that do nothing else: a register loop of "
+                                        "v_mfma_f32_16x16x32_bf16 on real operand data (power-limited), a plain streaming read"),
+               accepted_tokens_last_step=int(n_o.item()), walk=walk, t_sweep=sweep,
                roofline=roofline, other_rooflines=other, kernels=kernels)
 
     # ---------------- CPU oracle on a bounded sample ---------------------------------------------------
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, pk, pv, tok, par, dl, dc, c4, P, T, temperature, top_p)
     print(json.dumps(out), flush=True)
+
+
+def walk_block(sx, wl, torch, np, dev, cfg, tok, par, tok_d, par_d, pk, pv, tree_k, tree_v, P, temperature, top_p):
+    """accept_walk and commit_kv on crafted logits: the path to the deepest leaf is made overwhelmingly likely, so the
+    walk takes one step per level.  Returns steps walked and microseconds per walk step / per commit."""
+    T, V = len(tok), cfg.vocab
+    depth = np.zeros(T, dtype=np.int64)
+    for i in range(T):
+        depth[i] = 0 if par[i] < 0 else depth[par[i]] + 1
+    leaf, chain = int(np.argmax(depth)), []
+    while leaf >= 0:
+        chain.append(leaf)
+        leaf = int(par[leaf])
+    chain = chain[::-1]
+    lg = torch.randn((T, V), dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(5))
+    for a, b in zip(chain[:-1], chain[1:]):
+        lg[a, int(tok[b])] = 30.0          # the nucleus at node a is the token of its child on the chain
+    path_o = torch.empty(T, dtype=torch.int32, device=dev)
+    toks_o = torch.empty(T, dtype=torch.int32, device=dev)
+    n_o = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = torch.empty(sx.lib.sx_accept_walk_workspace(T, V), dtype=torch.uint8, device=dev)
+    reps, ev = 5, [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_walk = t_commit = 0.0
+    for r in range(reps + 1):               # first repetition untimed
+        ev[0].record()
+        sx.accept_walk(lg, tok_d, par_d, temperature, top_p, 11 + r, P, path_out=path_o, tokens_out=toks_o, n_out=n_o,
+                       workspace=ws)
+        ev[1].record()
+        sx.commit_kv(cfg, pk, pv, P, tree_k, tree_v, path_o, n_o)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if r:
+            t_walk += ev[0].elapsed_time(ev[1])
+            t_commit += ev[1].elapsed_time(ev[2])
+    n = int(n_o.item())
+    assert path_o[:n].cpu().tolist() == chain[:n] and n == len(chain), (n, len(chain))
+    return dict(steps=n, accepted_draft_tokens=n - 1, us_per_walk=round(t_walk / reps * 1e3, 2),
+                us_per_walk_step=round(t_walk / reps * 1e3 / n, 2), us_per_commit=round(t_commit / reps * 1e3, 2),
+                rows_committed_per_layer=n, logits="crafted: N(0,1) plus 30 on the next token of the path to the deepest leaf")
+
+
+def t_sweep(sx, wl, torch, np, dev, cfg, mw, pk, pv, P, k_tree, T_full):
+    """Forward time against tree size (the paper's Fig. 1, right, asks how the target's forward time grows with the
+    number of input tokens): sx_verify_tree alone on best-first trees of 256, 1024 and 2048 nodes, same model and prefix."""
+    out = []
+    for T in (256, 1024, T_full):
+        tok, par, _ = wl.gen_best_first_tree(T, k_tree, cfg.vocab, seed=3)
+        tok_d, par_d = torch.from_numpy(tok).to(dev), torch.from_numpy(par).to(dev)
+        logits = torch.empty((T, cfg.vocab), dtype=torch.float32, device=dev)
+        ws = torch.empty(sx.verify_tree_workspace(cfg, P, T), dtype=torch.uint8, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        for r in range(reps + 1):
+            if r == 1:
+                e0.record()
+            sx.verify_tree(mw, pk, pv, tok_d, par_d, logits_out=logits, workspace=ws, P=P)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        depth = np.zeros(T, dtype=np.int64)
+        for i in range(T):
+            depth[i] = 0 if par[i] < 0 else depth[par[i]] + 1
+        d, F, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+        Nq, Nkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        flop = cfg.n_layers * (2.0 * T * d * (Nq + 2 * Nkv) + 2.0 * T * Nq * d + 6.0 * T * d * F
+                               + 4.0 * Nq * float((P + depth + 1).sum())) + 2.0 * T * d * V
+        out.append(dict(T=T, ms=round(ms, 3), tokens_per_s=round(T / ms * 1e3, 1), tflops=round(flop / ms / 1e9, 1)))
+    return out
 
 
 def bench_draft(args, sx, wl, torch, np, dev):

@@ -111,9 +111,12 @@ def tensor_key(seed: int, *ids: int) -> int:
 
 
 def hash_normal(key: int, shape, std: float = 1.0, mean: float = 0.0, dtype=torch.float32,
-                device="cpu", chunk: int = 1 << 25) -> torch.Tensor:
-    """Bell-shaped (Irwin-Hall 8) pseudo-random tensor, identical on every device."""
+                device="cpu", chunk: int | None = None) -> torch.Tensor:
+    """Bell-shaped (Irwin-Hall 8) pseudo-random tensor, identical on every device (and for every chunk size:
+    the chunk only sets how much is computed at a time -- cache-sized pieces on a CPU, large ones on a GPU)."""
     n = int(np.prod(shape))
+    if chunk is None:
+        chunk = 1 << 18 if torch.device(device).type == "cpu" else 1 << 25
     out = torch.empty(n, dtype=dtype, device=device)
     scale = np.float32(std / _IH8_STD)
     k = _s64(key)
@@ -159,20 +162,24 @@ def gen_layer(cfg: ModelCfg, seed: int, layer: int, device="cpu") -> dict:
     return out
 
 
+def gen_model_ends(cfg: ModelCfg, seed: int, device="cpu") -> dict:
+    """What a model holds besides its layers: embed [V,d], final_norm [d], lm_head [V,d] (untied)."""
+    return dict(
+        embed=hash_normal(tensor_key(seed, 0, 0), (cfg.vocab, cfg.d_model), std=0.02, dtype=cfg.torch_dtype, device=device),
+        final_norm=hash_normal(tensor_key(seed, 0, 1), (cfg.d_model,), std=0.1, mean=1.0, dtype=cfg.torch_dtype,
+                               device=device),
+        lm_head=hash_normal(tensor_key(seed, 0, 2), (cfg.vocab, cfg.d_model), std=0.02, dtype=cfg.torch_dtype,
+                            device=device))
+
+
 def gen_weights(cfg: ModelCfg, seed: int, device="cpu", progress=None) -> dict:
     """Whole model: embed [V,d], layers[L], final_norm [d], lm_head [V,d] (untied)."""
-    w = dict(cfg=cfg)
-    w["embed"] = hash_normal(tensor_key(seed, 0, 0), (cfg.vocab, cfg.d_model), std=0.02,
-                             dtype=cfg.torch_dtype, device=device)
-    w["layers"] = []
+    w = dict(cfg=cfg, layers=[])
     for l in range(cfg.n_layers):
         w["layers"].append(gen_layer(cfg, seed, l, device))
         if progress is not None:
             progress(l)
-    w["final_norm"] = hash_normal(tensor_key(seed, 0, 1), (cfg.d_model,), std=0.1, mean=1.0,
-                                  dtype=cfg.torch_dtype, device=device)
-    w["lm_head"] = hash_normal(tensor_key(seed, 0, 2), (cfg.vocab, cfg.d_model), std=0.02,
-                               dtype=cfg.torch_dtype, device=device)
+    w.update(gen_model_ends(cfg, seed, device))
     return w
 
 
