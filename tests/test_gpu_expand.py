@@ -142,6 +142,20 @@ def test_full_size_draft_expansion(sx):
         np.testing.assert_array_equal(a, b)
 
 
+@pytest.mark.parametrize("N,V,k", [(600, 32000, 32), (513, 16388, 8), (700, 32768, 100), (1030, 20000, 64)])
+def test_many_rows_of_a_large_vocabulary(sx, N, V, k):
+    """More rows than the chip holds workgroups at a time (several rounds per compute unit) at vocabularies of
+    16k-32k: ragged row counts, a vocabulary that is not a multiple of the lanes' share, k above the one-wave
+    ordering, and rows that need the exact search in the middle of the launch; every row must come out as the
+    oracle's."""
+    logits, _ = wl.gen_expand_inputs(N, V, seed=N + V)
+    logits[N - 1, :] = 1.5                            # the last row: all ties
+    logits[N // 2, :] = np.round(logits[N // 2, :])   # heavy ties in the middle of the launch
+    logits[300, ::3] = -np.inf
+    logits[301, 7:7 + k + 5] = logits[301].max() + 2.0   # k cuts through a run of tied maxima
+    _check_rows(sx, logits, k)
+
+
 def test_shape_errors(sx):
     x = torch.zeros((4, 100), device=dev())
     c = torch.zeros(4, device=dev())

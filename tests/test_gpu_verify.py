@@ -517,3 +517,33 @@ def test_c2_llama7b_layer_full_parity(sx):
     err, q, floor, std = _bf16_model_parity(sx, c["cfg"], c["P"], c["T"], c["k"], seed=31)
     assert std > 1.0
     _assert_bf16_parity(err, q, floor)
+
+
+def test_verify_tree_repeats_bit_for_bit_where_tiles_are_cut_along_k(sx):
+    """Run-to-run determinism of the forward at a shape that takes the K split: one 70B-shaped layer over a
+    2048-node tree (the QKV projection then has 320 tiles on 256 compute units, the last 64 cut in two along K,
+    their partial sums added by whichever workgroup arrives last -- in part order, so the sum must not depend
+    on who that was).  Three runs, the scratch memory filled with different garbage before each: logits and
+    tree K/V identical to the last bit."""
+    cfg = wl.CONFIGS["C5"]["cfg"].with_layers(1)
+    T, P = 2048, 192
+    w = wl.gen_weights(cfg, seed=41, device=dev())
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=42, device=dev())
+    tok, par, _ = wl.gen_best_first_tree(T, 32, cfg.vocab, seed=43)
+    mw = sx.ModelWeights(cfg, w)
+    td, pd = to_dev(tok), to_dev(par)
+    ws = torch.empty(sx.verify_tree_workspace(cfg, P, T), dtype=torch.uint8, device=dev())
+    runs = []
+    for fill in (0, 0xA5, 0x3C):
+        ws.fill_(fill)
+        tk = torch.empty((1, T, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device=dev())
+        tv = torch.empty_like(tk)
+        logits, _ = sx.verify_tree(mw, pk, pv, td, pd, tree_k_out=tk, tree_v_out=tv, workspace=ws)
+        torch.cuda.synchronize()
+        assert sx.check_status(ws) == 0
+        runs.append((logits.clone(), tk, tv))
+    assert torch.isfinite(runs[0][0]).all() and float(runs[0][0].std()) > 1.0
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
+                               b.view(torch.int32) if b.dtype == torch.float32 else b.view(torch.int16))
