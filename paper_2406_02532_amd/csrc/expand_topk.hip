@@ -83,6 +83,7 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
   __shared__ int redi[16];
   __shared__ float s_t0;
   __shared__ int s_cnt;
+  __shared__ int s_part[NW][64];  // partial ranks / places, one row per wave
   __shared__ unsigned long long cand[kCandCap];
 
   const int tid = threadIdx.x;
@@ -126,27 +127,32 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
 #pragma unroll
   for (int w = 1; w < NW; ++w) M = fmaxf(M, redf[w]);
 
-  // ---- sum of exponentials; meanwhile wave 0 ranks the group maxima ---------------------------------
+  // ---- sum of exponentials, and the ranks of the group maxima ------------------------------------------
   // t0 = k-th largest of a set of group maxima (rank by value, then group id) is a lower bound of
-  // the k-th largest entry.  k <= 64: 64 groups ranked by one wave with lane broadcasts (hardly
-  // looser than per-lane maxima and far cheaper); else every lane is a group.
-  float se = 0.f;
+  // the k-th largest entry.  k <= 64: 64 groups (hardly looser than per-lane maxima and far cheaper),
+  // ranked with lane broadcasts by all waves together, each comparing the 64 maxima with its share of
+  // 64 / NW of them (all 64 broadcasts on one wave were the longest single-wave stretch of the kernel);
+  // the partial ranks meet in LDS at the next barrier.  Larger k: every lane is a group.
+  const int lane = tid & 63, wave = tid >> 6;
+  float gmine = 0.f;
+  if (small_k) {
+    gmine = s_gmax[lane];
+    int prank = 0;
 #pragma unroll
-  for (int e = 0; e < IPT4 * 4; ++e) se += __builtin_amdgcn_exp2f((v[e] - M) * kLog2e);
+    for (int jj = 0; jj < 64 / NW; ++jj) {
+      const int j = __builtin_amdgcn_readfirstlane(wave) * (64 / NW) + jj;
+      const float o = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gmine), j));
+      prank += (o > gmine || (o == gmine && j < lane)) ? 1 : 0;
+    }
+    s_part[wave][lane] = prank;
+  }
+  float se = 0.f;
+  const float mshift = -M * kLog2e;
+#pragma unroll
+  for (int e = 0; e < IPT4 * 4; ++e) se += __builtin_amdgcn_exp2f(fmaf(v[e], kLog2e, mshift));
   se = wave_sum(se);
   if ((tid & 63) == 0) redf[NW + (tid >> 6)] = se;
-  if (small_k) {
-    if (tid < 64) {
-      const float g = s_gmax[tid];
-      int rank = 0;
-#pragma unroll
-      for (int j = 0; j < 64; ++j) {
-        const float o = __shfl(g, j, 64);
-        rank += (o > g || (o == g && j < tid)) ? 1 : 0;
-      }
-      if (rank == k - 1) s_t0 = g;
-    }
-  } else {
+  if (!small_k) {
     int rank = 0;
     for (int j = 0; j < THREADS; ++j) {
       const float o = smax[j];
@@ -159,19 +165,28 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
 #pragma unroll
   for (int w = 0; w < NW; ++w) S += redf[NW + w];
   const float lse = M + logf(S);
-  const float t0 = s_t0;
+  float t0;
+  if (small_k) {  // exactly one group has rank k - 1 (ranks are a permutation of 0..63)
+    int rank = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) rank += s_part[w][lane];
+    const unsigned long long who = __builtin_amdgcn_ballot_w64(rank == k - 1);
+    t0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gmine), __builtin_ctzll(who)));
+  } else {
+    t0 = s_t0;
+  }
 
   // ---- gather candidates >= t0 ---------------------------------------------------------------
+  // Hits are rare (a few dozen per row): the four values of a register quad are looked at only where the
+  // quad's maximum of some lane of the wave reaches t0 -- two instructions and one scalar branch per quad.
 #pragma unroll
   for (int j = 0; j < IPT4; ++j) {
+    const float m4 = fmaxf(fmaxf(v[4 * j + 0], v[4 * j + 1]), fmaxf(v[4 * j + 2], v[4 * j + 3]));
+    if (__builtin_amdgcn_ballot_w64(m4 >= t0) != 0ull) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      // hits are rare (a few dozen per row): one compare and one scalar branch per register, and the
-      // divergent code only where some lane of the wave has one
-      const bool hit = v[4 * j + c] >= t0;
-      if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+      for (int c = 0; c < 4; ++c) {
         const int idx = (j * THREADS + tid) * 4 + c;
-        if (hit && idx < V) {
+        if (v[4 * j + c] >= t0 && idx < V) {
           const int pos = atomicAdd(&s_cnt, 1);
           if (pos < kCandCap)
             cand[pos] = ((unsigned long long)(~f32_order_key(v[4 * j + c])) << 32) | (unsigned)idx;
@@ -184,18 +199,25 @@ __global__ __launch_bounds__(THREADS) void row_topk_kernel(const float* __restri
   const float cl = cum_logp ? cum_logp[row] : 0.f;
 
   if (small_k && C <= 64) {
-    // ---- the usual case: a few dozen candidates, ordered by one wave in registers -------------------
-    if (tid >= 64) return;
-    // keys are distinct (the index is part of them), so a candidate's place is the number of smaller
-    // keys: 64 scalar broadcasts and compares, no sorting network and no cross-lane latency chain
-    const unsigned long long x64 = tid < C ? cand[tid] : ~0ull;
+    // ---- the usual case: a few dozen candidates, ordered in registers ------------------------------------
+    // Keys are distinct (the index is part of them), so a candidate's place is the number of smaller keys:
+    // scalar broadcasts and compares, no sorting network and no cross-lane latency chain.  Every wave holds
+    // all candidates (lane = candidate) and counts against its share of 64 / NW of them.
+    const unsigned long long x64 = lane < C ? cand[lane] : ~0ull;
     const unsigned xlo = (unsigned)x64, xhi = (unsigned)(x64 >> 32);
+    int pplace = 0;
+#pragma unroll
+    for (int jj = 0; jj < 64 / NW; ++jj) {
+      const int j = __builtin_amdgcn_readfirstlane(wave) * (64 / NW) + jj;
+      const unsigned olo = __builtin_amdgcn_readlane(xlo, j), ohi = __builtin_amdgcn_readlane(xhi, j);
+      pplace += (ohi < xhi || (ohi == xhi && olo < xlo)) ? 1 : 0;
+    }
+    s_part[wave][lane] = pplace;  // (the ranks in there were read before barrier (3))
+    __syncthreads();  // (4)
+    if (tid >= 64) return;
     int place = 0;
 #pragma unroll
-    for (int j = 0; j < 64; ++j) {
-      const unsigned olo = __builtin_amdgcn_readlane(xlo, j), ohi = __builtin_amdgcn_readlane(xhi, j);
-      place += (ohi < xhi || (ohi == xhi && olo < xlo)) ? 1 : 0;
-    }
+    for (int w = 0; w < NW; ++w) place += s_part[w][lane];
     if (tid < C && place < k) {
       const float val = f32_from_order_key(~xhi);
       const float lp = val - lse;
