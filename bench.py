@@ -74,6 +74,8 @@ def main():
                          "Llama-2-7B-shaped draft model (not the headline metric)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (development only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="draft7b only: also time the tree construction recorded once into a HIP graph and replayed")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB -> 1 GiB device copy after the timed steps, so that a counter run "
                          "of this command holds a dispatch of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -361,6 +363,35 @@ def bench_draft(args, sx, wl, torch, np, dev):
     torch.cuda.synchronize()
     assert sx.check_status(ws) == 0
     launches = D * (12 * cfg.n_layers + 24) + 8
+    graph_ms = capture_ms = None
+    if args.graph:
+        # the same call recorded once into a HIP graph (nothing in it allocates or synchronises) and replayed: what is
+        # left of the gaps between ~8000 short launches when the host does not launch them one by one
+        outs = (toks.clone(), par.clone(), cum.clone(), n.clone())
+        eager = [t.clone() for t in (toks, par, cum, n)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws, out=outs)   # warm on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        t0 = time.perf_counter()
+        with torch.cuda.graph(g, stream=side):
+            sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws, out=outs)
+        capture_ms = (time.perf_counter() - t0) * 1e3   # recording ~8000 launches and instantiating the graph (host time)
+        for rep in range(3):   # replays, with eager work and a synchronisation in between; every replay must give the eager tree
+            g.replay()
+            torch.cuda.synchronize()
+            for a, b in zip(outs, eager):
+                assert torch.equal(a, b), "graph replay differs from the eager call"
+            outs[0].zero_()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
     sx.profile_enable(launches * args.steps + 64)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -388,6 +419,8 @@ def bench_draft(args, sx, wl, torch, np, dev):
                                                                      cfg.d_ffn, cfg.vocab, P, K, D, B, k),
                     parameters_GB=round(nparam * 2 / 1e9, 1)),
         ms_per_iteration=round(ms / D, 3), tree=dict(nodes=nn, max_depth=int(depth.max())),
+        ms_per_tree_graph_replay=None if graph_ms is None else round(graph_ms, 3),
+        graph_capture_ms=None if capture_ms is None else round(capture_ms, 1),
         weight_streaming_floor_ms_per_iteration=round(nparam * 2 / 5.0e12 * 1e3, 3),
         kernels={k_: dict(launches_per_tree=v[0] / args.steps, ms_per_tree=round(v[1] / args.steps, 3))
                  for k_, v in sorted(agg.items(), key=lambda kv: -kv[1][1])})), flush=True)

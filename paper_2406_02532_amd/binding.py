@@ -244,15 +244,19 @@ def specexec_round(weights: ModelWeights, cache_k, cache_v, P: int, tree_tokens,
 
 
 def draft_tree(weights: ModelWeights, prefix_k, prefix_v, P: int, root_token, K: int, D: int, B: int, k: int,
-               workspace=None, stream=None):
-    """sx_draft_tree: (tokens [K], parent [K], cum_logp [K], n [1], workspace) -- device tensors, nothing synchronised."""
+               workspace=None, stream=None, out=None):
+    """sx_draft_tree: (tokens [K], parent [K], cum_logp [K], n [1], workspace) -- device tensors, nothing synchronised.
+    out: the first four, preallocated (then the call allocates nothing, e.g. under stream capture)."""
     cfg, dev = weights.cfg, weights.device
     c = _make_cfg(cfg)
     capacity = 0 if prefix_k is None else int(prefix_k.shape[1])
-    toks = torch.zeros(K, dtype=torch.int32, device=dev)
-    par = torch.zeros(K, dtype=torch.int32, device=dev)
-    cum = torch.zeros(K, dtype=torch.float32, device=dev)
-    n = torch.zeros(1, dtype=torch.int32, device=dev)
+    if out is not None:
+        toks, par, cum, n = out
+    else:
+        toks = torch.zeros(K, dtype=torch.int32, device=dev)
+        par = torch.zeros(K, dtype=torch.int32, device=dev)
+        cum = torch.zeros(K, dtype=torch.float32, device=dev)
+        n = torch.zeros(1, dtype=torch.int32, device=dev)
     if workspace is None:
         nbytes = lib.sx_draft_tree_workspace(C.byref(c), P, K, D, B, k)
         if nbytes == 0:

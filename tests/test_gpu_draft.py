@@ -224,3 +224,42 @@ def test_draft_tree_degenerate_budgets(sx, draft):
     n = int(n.item())
     assert n == len(ref["tokens"]) == 4
     assert toks[:n].cpu().tolist() == ref["tokens"].tolist() and par[:n].cpu().tolist() == ref["parent"].tolist()
+
+
+def test_draft_tree_recorded_in_a_graph_replays_the_eager_result(sx):
+    """sx_draft_tree only enqueues kernels (no allocation, no host synchronisation, no memset nodes), so a caller
+    may record it into a HIP graph and replay it, which removes the gaps between its thousands of short launches.
+    A bf16 draft model (the narrow GEMMs with K cut among workgroups, whose counters must be left clean for the
+    next replay): three replays, each after eager work and a synchronisation, each equal to the eager call."""
+    cfg = wl.ModelCfg(3, 512, 8, 2, 128, 1408, 2000, dtype="bf16")
+    K, D, B, k, P = 96, 6, 32, 6, 80
+    w = wl.gen_weights(cfg, seed=71, device=dev())
+    w["lm_head"] = (w["lm_head"].float() * 10).to(torch.bfloat16)
+    mw = sx.ModelWeights(cfg, w)
+    pk, pv = wl.gen_prefix_kv(cfg, P, seed=72, device=dev())
+    root = torch.tensor([41], dtype=torch.int32, device=dev())
+    toks, par, cum, n, ws = sx.draft_tree(mw, pk, pv, P, root, K, D, B, k)
+    torch.cuda.synchronize()
+    assert sx.check_status(ws) == 0 and int(n.item()) > 8
+    eager = [t.clone() for t in (toks, par, cum, n)]
+    outs = tuple(torch.zeros_like(t) for t in eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws, out=outs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        sx.draft_tree(mw, pk, pv, P, root, K, D, B, k, workspace=ws, out=outs)
+    for rep in range(3):
+        for t in outs:
+            t.zero_()                                    # eager work between the replays
+        junk = torch.randn(1 << 20, device=dev()).sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert sx.check_status(ws) == 0
+        for a, b in zip(outs, eager):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager call"
+    del junk
