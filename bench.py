@@ -74,6 +74,7 @@ def main():
                          "Llama-2-7B-shaped draft model (not the headline metric)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (development only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--w4", action="store_true", help="draft7b only: the draft model's decoder layers in 4 bits")
     ap.add_argument("--graph", action="store_true",
                     help="draft7b only: also time the tree construction recorded once into a HIP graph and replayed")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -354,6 +355,11 @@ def bench_draft(args, sx, wl, torch, np, dev):
     K, D, B, k, P = 2048, 24, 128, 32, 2048
     w = wl.gen_weights(cfg, seed=5, device=dev)
     w["lm_head"] = (w["lm_head"].float() * 8).to(torch.bfloat16)      # sharper next-token distributions than N(0, 0.02)
+    if args.w4:   # the same shape with 4-bit decoder layers (random codes, group 128); embed, norms and lm_head stay bf16
+        w["layers_w4"] = wl.gen_w4_layers(cfg, 128, seed=7, device=dev)
+        w["w4_group"] = 128
+        w["layers"] = [{n: lw[n] for n in ("attn_norm", "ffn_norm")} for lw in w["layers"]]
+        torch.cuda.empty_cache()
     mw = sx.ModelWeights(cfg, w)
     pk, pv = wl.gen_prefix_kv(cfg, P, seed=6, device=dev)
     root = torch.tensor([17], dtype=torch.int32, device=dev)
@@ -410,6 +416,9 @@ def bench_draft(args, sx, wl, torch, np, dev):
     for i in range(1, nn):
         depth[i] = depth[par_h[i]] + 1
     nparam = sum(v.numel() for lw in w["layers"] for v in lw.values()) + w["embed"].numel() + w["lm_head"].numel()
+    weight_bytes = nparam * 2
+    if args.w4:
+        weight_bytes += sum(t.numel() * t.element_size() for lq in w["layers_w4"] for m in lq.values() for t in m)
     print(json.dumps(dict(
         metric="draft tree construction time (side measurement, not the headline)", value=round(ms, 3), unit="ms",
         n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms, 3), higher_is_better=False, scaling="weak",
@@ -417,11 +426,12 @@ def bench_draft(args, sx, wl, torch, np, dev):
         config=dict(workload="draft7b: %d-layer Llama-2-7B-shaped draft (d=%d, %d heads x %d, FFN %d, vocab %d), prefix %d, "
                              "sx_draft_tree K=%d D=%d B=%d k=%d" % (cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.head_dim,
                                                                      cfg.d_ffn, cfg.vocab, P, K, D, B, k),
-                    parameters_GB=round(nparam * 2 / 1e9, 1)),
+                    weights="4-bit decoder layers (group 128), bf16 embed / lm_head" if args.w4 else "bf16",
+                    parameters_GB=round(weight_bytes / 1e9, 1)),
         ms_per_iteration=round(ms / D, 3), tree=dict(nodes=nn, max_depth=int(depth.max())),
         ms_per_tree_graph_replay=None if graph_ms is None else round(graph_ms, 3),
         graph_capture_ms=None if capture_ms is None else round(capture_ms, 1),
-        weight_streaming_floor_ms_per_iteration=round(nparam * 2 / 5.0e12 * 1e3, 3),
+        weight_streaming_floor_ms_per_iteration=round(weight_bytes / 5.0e12 * 1e3, 3),
         kernels={k_: dict(launches_per_tree=v[0] / args.steps, ms_per_tree=round(v[1] / args.steps, 3))
                  for k_, v in sorted(agg.items(), key=lambda kv: -kv[1][1])})), flush=True)
 

@@ -72,12 +72,36 @@ typedef struct sx_layer_weights {
   const void *w_down;    /* [d][F] */
 } sx_layer_weights;
 
+/* A weight matrix W [N][K] stored in 4 bits (Sect. 5: the paper's fastest setting runs its models quantised to
+ * 4 bits; it names the quantiser and leaves the storage open -- this is the common group-wise one): codes 0..15,
+ * eight per 32-bit word (code j of word i of a row is k = 8 i + j, bits 4j..4j+3); per row and group of `group`
+ * consecutive k one bf16 scale and one zero point 0..15 (a byte); w = bf16(scale * (code - zero)), the product exact
+ * in fp32 and rounded once.  All device pointers. */
+typedef struct sx_w4_matrix {
+  const void *qweight; /* uint32 [N][K/8] */
+  const void *scales;  /* bf16   [N][K/group] */
+  const void *zeros;   /* uint8  [N][K/group] */
+} sx_w4_matrix;
+
+/* The seven linear layers of one decoder layer in 4 bits (shapes as in sx_layer_weights). */
+typedef struct sx_layer_weights_w4 {
+  sx_w4_matrix wq, wk, wv, wo, w_gate, w_up, w_down;
+} sx_layer_weights_w4;
+
 typedef struct sx_weights {
   sx_model_cfg cfg;
   const void *embed;              /* device [V][d] */
   const sx_layer_weights *layers; /* HOST array of n_layers structs holding device pointers */
   const void *final_norm;         /* device [d] */
   const void *lm_head;            /* device [V][d] */
+  /* Optional 4-bit decoder layers (cfg.dtype must be SX_BF16).  NULL: the bf16 matrices of `layers` are used.
+   * Not NULL: HOST array of n_layers structs; every linear layer of the decoder then takes its weights from here
+   * (the matrix pointers in `layers` may be NULL; the norm gains still come from there), embed and lm_head stay
+   * bf16, activations and all arithmetic are as in the bf16 model with w in place of the bf16 weight.  w4_group:
+   * the group size, a power of two >= 64 that divides d_model, Hq*Dh and d_ffn; d_model, Hq*Dh and d_ffn must
+   * then be multiples of 128 (64 for calls with at most 128 query nodes). */
+  const sx_layer_weights_w4 *layers_w4;
+  int32_t w4_group;
 } sx_weights;
 
 /* ------------------------------------------------------------------------------------------
@@ -106,6 +130,13 @@ typedef struct sx_weights {
  * stream, softmax and norm statistics, and all accumulation are fp32.
  * ---------------------------------------------------------------------------------------- */
 size_t sx_verify_tree_workspace(const sx_model_cfg *cfg, int32_t P, int32_t T);
+/* Workspace of the same calls when w->layers_w4 is set (4-bit decoder layers, Sect. 5).  With at most 128 query
+ * nodes per call (the draft model's batches) the linear layers read the 4-bit weights directly -- dequantised in
+ * registers on the way to the matrix cores, the regime where fewer weight bytes mean less time -- and this equals
+ * sx_verify_tree_workspace.  With more query nodes the product is bound by the matrix cores, not by weight bytes:
+ * each layer's seven matrices are then expanded to bf16 once per call into a scratch behind the ordinary
+ * workspace (one layer's worth: 1.7 GB for a 70B-shaped layer) and the bf16 kernels run on that copy. */
+size_t sx_verify_tree_w4_workspace(const sx_model_cfg *cfg, int32_t P, int32_t T);
 int sx_verify_tree(const sx_weights *w, const void *prefix_k, const void *prefix_v, int32_t P,
                    const int32_t *tree_tokens, const int32_t *parent_idx, int32_t T,
                    float *logits_out, void *tree_k_out, void *tree_v_out, void *workspace,
@@ -255,7 +286,8 @@ int sx_specexec_round(const sx_weights *w, void *cache_k, void *cache_v, int32_t
  *                       int32 [1] (1 <= n <= K).  Nodes in order of insertion (parents before
  *                       children, node 0 = root with parent -1): the input sx_verify_tree expects.
  * Supported: D * B <= 16384, k <= 256 (k is clamped to the vocabulary), min(K, B k) <= 8192,
- * K + min(K, B k) <= 16384, and the model shapes of sx_verify_tree with T = D * B.
+ * K + min(K, B k) <= 16384, and the model shapes of sx_verify_tree with T = D * B.  A draft model with 4-bit
+ * layers (w->layers_w4) needs B <= 128 (its batches then read the 4-bit weights directly; no scratch copy).
  * workspace: sx_draft_tree_workspace bytes, 256-byte aligned; sx_check_status on it reports an error of
  * any of the D forward passes (the first pass resets the status word, the later ones leave an error in place).
  * ---------------------------------------------------------------------------------------- */

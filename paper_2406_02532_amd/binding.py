@@ -8,7 +8,7 @@ import os
 import torch
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec_mi.so")
-EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
+EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree_w4_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
            "sx_specexec_round_workspace", "sx_specexec_round", "sx_draft_tree_workspace", "sx_draft_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_expand_topk_static", "sx_check_status", "sx_status_string", "sx_version",
            "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_gemm_w4a16_workspace", "sx_gemm_w4a16_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
@@ -35,9 +35,20 @@ class _Layer(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
 
 
+class _W4Matrix(C.Structure):
+    _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p)]
+
+
+_W4_FIELDS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+class _LayerW4(C.Structure):
+    _fields_ = [(n, _W4Matrix) for n in _W4_FIELDS]
+
+
 class _Weights(C.Structure):
     _fields_ = [("cfg", _Cfg), ("embed", C.c_void_p), ("layers", C.POINTER(_Layer)), ("final_norm", C.c_void_p),
-                ("lm_head", C.c_void_p)]
+                ("lm_head", C.c_void_p), ("layers_w4", C.POINTER(_LayerW4)), ("w4_group", C.c_int32)]
 
 
 def _load():
@@ -48,6 +59,8 @@ def _load():
     vp, i32, f32, u64, sz = C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_size_t
     L.sx_verify_tree_workspace.restype = sz
     L.sx_verify_tree_workspace.argtypes = [C.POINTER(_Cfg), i32, i32]
+    L.sx_verify_tree_w4_workspace.restype = sz
+    L.sx_verify_tree_w4_workspace.argtypes = [C.POINTER(_Cfg), i32, i32]
     L.sx_verify_tree.restype = C.c_int
     L.sx_verify_tree.argtypes = [C.POINTER(_Weights), vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.sx_accept_walk_workspace.restype = sz
@@ -147,20 +160,40 @@ def _make_cfg(cfg) -> _Cfg:
 
 class ModelWeights:
     """sx_weights built from a dict of device tensors (embed, layers[list of dict], final_norm, lm_head).
-    Holds references to the tensors so the pointers stay valid."""
+    Holds references to the tensors so the pointers stay valid.  4-bit decoder layers: w["layers_w4"] = list of
+    dicts name -> (qweight int32/uint32 [N][K/8], scales bf16 [N][K/group], zeros uint8 [N][K/group]) and
+    w["w4_group"]; the bf16 matrices of `layers` may then be missing (the norm gains are still needed)."""
 
     def __init__(self, cfg, w: dict):
         self.cfg = cfg
         self._keep = w
+        self.w4 = w.get("layers_w4") is not None
         self._layers = (_Layer * cfg.n_layers)()
         for l, lw in enumerate(w["layers"]):
             for n in _LAYER_FIELDS:
-                t = lw[n]
+                t = lw.get(n)
+                if t is None:
+                    assert self.w4 and not n.endswith("_norm"), n
+                    continue
                 assert t.is_contiguous() and t.dtype == cfg.torch_dtype
                 setattr(self._layers[l], n, t.data_ptr())
+        self._layers_w4 = None
+        if self.w4:
+            self._layers_w4 = (_LayerW4 * cfg.n_layers)()
+            for l, lq in enumerate(w["layers_w4"]):
+                for n in _W4_FIELDS:
+                    q, s, z = lq[n]
+                    assert q.is_contiguous() and s.is_contiguous() and z.is_contiguous()
+                    assert q.dtype in (torch.int32, torch.uint32) and s.dtype == torch.bfloat16 and z.dtype == torch.uint8
+                    setattr(self._layers_w4[l], n, _W4Matrix(q.data_ptr(), s.data_ptr(), z.data_ptr()))
         self.c = _Weights(_make_cfg(cfg), w["embed"].data_ptr(), self._layers, w["final_norm"].data_ptr(),
-                          w["lm_head"].data_ptr())
+                          w["lm_head"].data_ptr(), self._layers_w4, int(w.get("w4_group", 0)))
         self.device = w["embed"].device
+
+    def workspace_bytes(self, P: int, T: int) -> int:
+        c = _make_cfg(self.cfg)
+        f = lib.sx_verify_tree_w4_workspace if self.w4 else lib.sx_verify_tree_workspace
+        return f(C.byref(c), P, T)
 
 
 def verify_tree_workspace(cfg, P: int, T: int) -> int:
@@ -178,7 +211,7 @@ def verify_tree(weights: ModelWeights, prefix_k, prefix_v, tree_tokens, parent_i
     if logits_out is None:
         logits_out = torch.empty((T, cfg.vocab), dtype=torch.float32, device=weights.device)
     if workspace is None:
-        workspace = _workspace(verify_tree_workspace(cfg, P, T), weights.device)
+        workspace = _workspace(weights.workspace_bytes(P, T), weights.device)
     rc = lib.sx_verify_tree_cached(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), capacity, P, _ptr(tree_tokens),
                                    _ptr(parent_idx), T, _ptr(logits_out), _ptr(tree_k_out), _ptr(tree_v_out),
                                    _ptr(workspace), workspace.numel(), _stream(stream))
@@ -196,7 +229,7 @@ def verify_tree_range(weights: ModelWeights, prefix_k, prefix_v, P: int, tree_to
     if logits_out is None:
         logits_out = torch.empty((T - first, cfg.vocab), dtype=torch.float32, device=weights.device)
     if workspace is None:
-        workspace = _workspace(verify_tree_workspace(cfg, P, T), weights.device)
+        workspace = _workspace(weights.workspace_bytes(P, T), weights.device)
     rc = lib.sx_verify_tree_range(C.byref(weights.c), _ptr(prefix_k), _ptr(prefix_v), capacity, P, _ptr(tree_tokens),
                                   _ptr(parent_idx), T, first, _ptr(logits_out), _ptr(tree_k), _ptr(tree_v),
                                   int(tree_k.shape[1]), _ptr(workspace), workspace.numel(), _stream(stream))

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecexec_mi.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["expand_topk.hip", "accept_walk.hip", "tree_prep.hip", "elementwise.hip", "path_f32.hip",
-           "gemm_bf16.hip", "gemm_skinny_bf16.hip", "gemm_skinny_w4.hip", "tree_attn_bf16.hip", "verify_tree.hip", "draft_tree.hip", "prof.hip"]
+           "gemm_bf16.hip", "gemm_skinny_bf16.hip", "gemm_skinny_w4.hip", "gemm_w4_regs.hip", "tree_attn_bf16.hip", "verify_tree.hip", "draft_tree.hip", "prof.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -306,6 +306,7 @@ extern "C" int sx_draft_tree(const sx_weights* w, const void* prefix_k, const vo
   if (!w || !root_token || !tree_tokens_out || !parent_out || !cum_logp_out || !n_out) return SX_ERR_NULL;
   const sx_model_cfg& c = w->cfg;
   if (!draft_shape_ok(c, P, K, D, B, k) || capacity < P) return SX_ERR_SHAPE;
+  if (w->layers_w4 && B > 128) return SX_ERR_SHAPE;  // wider batches of a 4-bit model would need the bf16 scratch copy
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
   const DraftLayout L = draft_carve(c, P, K, D, B, k, workspace);
   if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;

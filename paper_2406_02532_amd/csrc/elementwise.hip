@@ -119,6 +119,36 @@ __global__ void swiglu_f32_kernel(const float* __restrict__ g, const float* __re
   }
 }
 
+// act[i][f] = bf16(silu(gu[i][f]) * gu[i][F + f]): the SwiGLU of a gate|up product kept in fp32 (4-bit path)
+__global__ void swiglu_pair_bf16_kernel(const float* __restrict__ gu, int n, int F, unsigned short* __restrict__ act) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * F) return;
+  const size_t i = idx / F, f = idx % F;
+  const float g = gu[i * 2 * F + f], u = gu[i * 2 * F + F + f];
+  act[idx] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
+}
+
+// One 32-bit word of eight 4-bit codes per thread -> eight bf16 weights w = bf16(scale * (code - zero)) (16 bytes).
+__global__ void dequant_w4_kernel(const uint32_t* __restrict__ q, const unsigned short* __restrict__ sc,
+                                  const unsigned char* __restrict__ zr, size_t words, int words_per_row, int group_log2,
+                                  int groups_per_row, unsigned short* __restrict__ W) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= words) return;
+  const size_t row = idx / words_per_row;
+  const int wi = (int)(idx % words_per_row);
+  const size_t g = row * groups_per_row + ((wi * 8) >> group_log2);
+  const float s = bf16_bits_to_f32(sc[g]);
+  const float z = (float)zr[g];
+  const uint32_t v = q[idx];
+  u32x4 o;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const float e = (float)((int)((v >> (8 * b)) & 15u)) - z, f = (float)((int)((v >> (8 * b + 4)) & 15u)) - z;
+    o[b] = pack_bf16x2(e * s, f * s);  // exact products (8 significant bits times at most 5), rounded once
+  }
+  *reinterpret_cast<u32x4*>(W + idx * 8) = o;
+}
+
 __global__ void zero_i32_kernel(int32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -164,6 +194,24 @@ int sx_launch_rope_split(const float* qkv, const float2* rope_cs, int T, int Hq,
 
 int sx_launch_zero_i32(int32_t* p, int n, hipStream_t s) {
   zero_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, n);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_swiglu_pair_bf16(const float* gu, int n, int F, void* act, hipStream_t s) {
+  const size_t total = (size_t)n * F;
+  swiglu_pair_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(gu, n, F, (unsigned short*)act);
+  SX_LAUNCH_CHECK();
+  return SX_OK;
+}
+
+int sx_launch_dequant_w4(const sx_w4_matrix* m, int N, int K, int group, void* W_bf16, hipStream_t s) {
+  if (!m || !m->qweight || !m->scales || !m->zeros || !W_bf16) return SX_ERR_NULL;
+  if (N < 1 || K < 8 || K % 8 != 0 || group < 8 || (group & (group - 1)) != 0 || K % group != 0) return SX_ERR_SHAPE;
+  const size_t words = (size_t)N * (K / 8);
+  dequant_w4_kernel<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(
+      (const uint32_t*)m->qweight, (const unsigned short*)m->scales, (const unsigned char*)m->zeros, words, K / 8,
+      __builtin_ctz((unsigned)group), K / group, (unsigned short*)W_bf16);
   SX_LAUNCH_CHECK();
   return SX_OK;
 }

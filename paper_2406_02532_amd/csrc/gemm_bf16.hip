@@ -361,19 +361,30 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     }
     __syncthreads();
     if (!s_last) return;
+    // Read back in batches of 16 blocks per part, all loads of a batch in flight together: one memory round
+    // trip per batch and part instead of one per block (a block at a time, the 64 dependent round trips were
+    // most of what the split cost).  Parts are added in part order whatever the batch size.
     const unsigned all = (unsigned)((tail_tile * ksplit * 4 + wave) * (64 * 256) + lane * 4) * 4u;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int b0 = 0; b0 < 64; b0 += 16) {
+      f32x4 sum[16];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        f32x4 sum = __builtin_bit_cast(
-            f32x4, __builtin_amdgcn_raw_buffer_load_b128(pres, all + (i * 8 + j) * 1024, 0, kScopeDevice));
-        for (int p = 1; p < ksplit; ++p)
-          sum += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                                               pres, all + (unsigned)p * (4u * 64 * 256 * 4) + (i * 8 + j) * 1024, 0,
+      for (int b = 0; b < 16; ++b)
+        sum[b] = __builtin_bit_cast(
+            f32x4, __builtin_amdgcn_raw_buffer_load_b128(pres, all + (b0 + b) * 1024, 0, kScopeDevice));
+      for (int p = 1; p < ksplit; ++p) {
+        f32x4 t[16];
+#pragma unroll
+        for (int b = 0; b < 16; ++b)
+          t[b] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                               pres, all + (unsigned)p * (4u * 64 * 256 * 4) + (b0 + b) * 1024, 0,
                                                kScopeDevice));
-        acc[i][j] = sum;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) sum[b] += t[b];
       }
+#pragma unroll
+      for (int b = 0; b < 16; ++b) acc[(b0 + b) >> 3][(b0 + b) & 7] = sum[b];
+    }
   }
 
   // ---- epilogue.  acc[i][j][e]: output row 16 j + l16 of the quadrant, W row 16 i + 4 lq + e ---------

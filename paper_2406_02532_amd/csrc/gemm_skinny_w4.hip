@@ -295,7 +295,7 @@ int sx_launch_gemm_skinny_w4(const void* X, const void* qweight, const void* sca
   return SX_OK;
 }
 
-extern "C" size_t sx_gemm_w4a16_workspace(void) { return 1024 + (size_t)256 * 8 * kPartFloats * sizeof(float); }
+extern "C" size_t sx_gemm_w4a16_workspace(void) { return sx_gemm_split_workspace(); }
 
 extern "C" int sx_gemm_w4a16_bf16(const void* X, const void* qweight, const void* scales, const void* zeros, void* Y,
                                   int32_t M, int32_t N, int32_t K, int32_t group, int32_t mode, void* workspace,
@@ -305,6 +305,12 @@ extern "C" int sx_gemm_w4a16_bf16(const void* X, const void* qweight, const void
   if (workspace) {
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < 1024) return SX_ERR_WORKSPACE;
     SX_TRY(sx_launch_zero_i32(static_cast<int32_t*>(workspace), 256, st));  // the K-split counters
+  }
+  // K a multiple of 128: weights dequantised in registers; otherwise through LDS
+  if (M >= 1 && M <= 128 && K >= 128 && K % 128 == 0 && N >= 1) {
+    const sx_w4_matrix m = {qweight, scales, zeros};
+    const int n = N;
+    return sx_launch_gemm_w4_regs(X, &m, &n, 1, group, static_cast<float*>(Y), N, M, K, mode, workspace, workspace_bytes, st);
   }
   return sx_launch_gemm_skinny_w4(X, qweight, scales, zeros, group, Y, M, N, K, mode, workspace, workspace_bytes, st);
 }

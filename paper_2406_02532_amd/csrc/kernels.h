@@ -63,6 +63,19 @@ size_t sx_gemm_split_workspace();
 int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, const void* Wv, int hq, int hkv,
                                  const float2* rope_cs, void* q, void* k, void* v, int M, int K, void* split_ws,
                                  size_t split_ws_bytes, hipStream_t st);
+// 4-bit weights (gemm_w4_regs.hip, gemm_skinny_w4.hip, elementwise.hip) -----------------------------------------------
+// Stacked 4-bit matrices (n_mats <= 3, every non-final one a multiple of 64 rows), M <= 128, K % 128 == 0: weights
+// dequantised in registers on the way to the matrix cores.  Y fp32 [M][ldy].  SX_ERR_SHAPE for other shapes.
+int sx_launch_gemm_w4_regs(const void* X, const sx_w4_matrix* mats, const int* ns, int n_mats, int group, float* Y, int ldy,
+                           int M, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st);
+// The older form (weights dequantised into LDS; M <= 128, K % 64 == 0, one matrix, Y fp32 [M][N] contiguous).
+int sx_launch_gemm_skinny_w4(const void* X, const void* qweight, const void* scales, const void* zeros, int group,
+                             void* Y, int M, int N, int K, int mode, void* split_ws, size_t split_ws_bytes, hipStream_t st);
+// W bf16 [N][K] = the dequantised matrix (for the wide GEMM, which is bound by the matrix cores and gains nothing
+// from reading fewer bytes).
+int sx_launch_dequant_w4(const sx_w4_matrix* m, int N, int K, int group, void* W_bf16, hipStream_t st);
+// act bf16 [n][F] = silu(gu[:, :F]) * gu[:, F:], gu fp32 [n][2F]
+int sx_launch_swiglu_pair_bf16(const float* gu, int n, int F, void* act, hipStream_t st);
 // n int32 zeros (a fill kernel: safe to capture in a graph, unlike a memset node)
 int sx_launch_zero_i32(int32_t* p, int n, hipStream_t st);
 // q and out hold Tq query nodes; k_tree / v_tree hold all T nodes of the tree; klist rows have stride T.

@@ -12,7 +12,7 @@ struct Layout {
   int32_t *tok_s, *par_s, *depth, *klist, *kcnt;
   float2* rope_cs;
   unsigned long long* rowmask;
-  float *h, *qkv, *gate, *up;
+  float *h, *qkv, *gate, *up, *gu;
   void *x, *q, *o, *act, *tk, *tv;
   void* split_ws;
   size_t split_bytes;
@@ -52,9 +52,12 @@ Layout carve(const sx_model_cfg& c, int P, int T, void* ws) {
     L.kcnt = cv.take<int32_t>(tiles);
     L.rowmask = cv.take<unsigned long long>((size_t)T * ((T + 63) / 64));
     L.gate = L.up = nullptr;
+    // gate|up product in fp32 of a batch of at most 128 nodes: the 4-bit kernels leave the SwiGLU to a kernel of its own
+    L.gu = cv.take<float>((size_t)(T < 128 ? T : 128) * 2 * c.d_ffn);
   } else {
     L.klist = L.kcnt = nullptr;
     L.rowmask = nullptr;
+    L.gu = nullptr;
     L.gate = cv.take<float>((size_t)T * c.d_ffn);
     L.up = cv.take<float>((size_t)T * c.d_ffn);
   }
@@ -78,6 +81,28 @@ int check_cfg(const sx_model_cfg& c, int P, int T) {
   return SX_OK;
 }
 
+// bf16 copy of one decoder layer's seven matrices (4-bit weights, more than 128 query nodes: the wide GEMM is bound by
+// the matrix cores, so the weights are expanded once per layer into this scratch and the bf16 kernels run unchanged)
+size_t w4_layer_scratch_bytes(const sx_model_cfg& c) {
+  const size_t Nq = (size_t)c.n_q_heads * c.head_dim, Nkv = (size_t)c.n_kv_heads * c.head_dim, d = c.d_model, F = c.d_ffn;
+  return sx_align_up((Nq * d + 2 * Nkv * d + d * Nq + 3 * F * d) * 2, 256);
+}
+
+int check_w4(const sx_weights& w) {
+  const sx_model_cfg& c = w.cfg;
+  if (c.dtype != SX_BF16) return SX_ERR_DTYPE;
+  const int g = w.w4_group, Nq = c.n_q_heads * c.head_dim;
+  if (g < 64 || (g & (g - 1)) != 0 || c.d_model % g != 0 || Nq % g != 0 || c.d_ffn % g != 0) return SX_ERR_SHAPE;
+  if (c.d_model % 128 != 0 || Nq % 128 != 0 || c.d_ffn % 128 != 0) return SX_ERR_SHAPE;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const sx_layer_weights_w4& q = w.layers_w4[l];
+    const sx_w4_matrix* m[7] = {&q.wq, &q.wk, &q.wv, &q.wo, &q.w_gate, &q.w_up, &q.w_down};
+    for (int i = 0; i < 7; ++i)
+      if (!m[i]->qweight || !m[i]->scales || !m[i]->zeros) return SX_ERR_NULL;
+  }
+  return SX_OK;
+}
+
 // same, bracketed by the optional event timer
 #define SX_TIMED(tag, expr)   \
   do {                        \
@@ -92,6 +117,12 @@ int check_cfg(const sx_model_cfg& c, int P, int T) {
 extern "C" size_t sx_verify_tree_workspace(const sx_model_cfg* cfg, int32_t P, int32_t T) {
   if (!cfg || check_cfg(*cfg, P, T) != SX_OK) return 0;
   return carve(*cfg, P, T, nullptr).bytes;
+}
+
+extern "C" size_t sx_verify_tree_w4_workspace(const sx_model_cfg* cfg, int32_t P, int32_t T) {
+  const size_t base = sx_verify_tree_workspace(cfg, P, T);
+  if (base == 0 || cfg->dtype != SX_BF16) return 0;
+  return sx_align_up(base, 256) + (T > 128 ? w4_layer_scratch_bytes(*cfg) : 0);
 }
 
 extern "C" int sx_verify_tree(const sx_weights* w, const void* prefix_k, const void* prefix_v, int32_t P,
@@ -131,14 +162,23 @@ int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const v
   SX_TRY(check_cfg(c, P, T));
   if (P > 0 && (!prefix_k || !prefix_v)) return SX_ERR_NULL;
   if ((tree_k_out == nullptr) != (tree_v_out == nullptr)) return SX_ERR_NULL;
+  const bool w4 = w->layers_w4 != nullptr;
+  if (w4) SX_TRY(check_w4(*w));
   for (int l = 0; l < c.n_layers; ++l) {
     const sx_layer_weights& lw = w->layers[l];
-    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
-      return SX_ERR_NULL;
+    if (!lw.attn_norm || !lw.ffn_norm) return SX_ERR_NULL;
+    if (!w4 && (!lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.w_gate || !lw.w_up || !lw.w_down)) return SX_ERR_NULL;
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
   const Layout L = carve(c, P, T, workspace);
   if (workspace_bytes < L.bytes) return SX_ERR_WORKSPACE;
+  // 4-bit weights and a wide batch: room for one layer's bf16 copy behind the ordinary workspace
+  char* w4_scratch = nullptr;
+  if (w4 && n > 128) {
+    const size_t at = sx_align_up(L.bytes, 256);
+    if (workspace_bytes < at + w4_layer_scratch_bytes(c)) return SX_ERR_WORKSPACE;
+    w4_scratch = static_cast<char*>(workspace) + at;
+  }
 
   hipStream_t st = (hipStream_t)stream;
   const bool bf = c.dtype == SX_BF16;
@@ -159,7 +199,27 @@ int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const v
   if (split_ws) SX_TRY(sx_launch_zero_i32(reinterpret_cast<int32_t*>(split_ws), 256, st));  // K-split counters
 
   for (int l = 0; l < c.n_layers; ++l) {
-    const sx_layer_weights& lw = w->layers[l];
+    sx_layer_weights lw = w->layers[l];
+    const sx_layer_weights_w4* q4 = w4 ? &w->layers_w4[l] : nullptr;
+    if (w4_scratch) {  // expand this layer's matrices; from here on the layer looks like a bf16 one
+      char* at = w4_scratch;
+      auto expand = [&](const sx_w4_matrix& m, int N, int K, const void** slot) -> int {
+        SX_TRY(sx_launch_dequant_w4(&m, N, K, w->w4_group, at, st));
+        *slot = at;
+        at += (size_t)N * K * 2;
+        return SX_OK;
+      };
+      sx_prof_begin(SX_K_NORM, st);  // (timed with the other bandwidth-bound kernels of the layer)
+      SX_TRY(expand(q4->wq, Nq, d, &lw.wq));
+      SX_TRY(expand(q4->wk, Nkv, d, &lw.wk));
+      SX_TRY(expand(q4->wv, Nkv, d, &lw.wv));
+      SX_TRY(expand(q4->wo, d, Nq, &lw.wo));
+      SX_TRY(expand(q4->w_gate, F, d, &lw.w_gate));
+      SX_TRY(expand(q4->w_up, F, d, &lw.w_up));
+      SX_TRY(expand(q4->w_down, d, F, &lw.w_down));
+      sx_prof_end(st);
+      q4 = nullptr;
+    }
     const size_t kv_layer = (size_t)l * tree_capacity * Nkv * es, pre_layer = (size_t)l * capacity * Nkv * es;
     // this layer's K/V of all tree nodes (keys of the attention) and where this call's nodes go in them
     char* tkb = tree_k_out ? static_cast<char*>(tree_k_out) + kv_layer : static_cast<char*>(L.tk);
@@ -173,7 +233,12 @@ int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const v
     // the wide GEMM's epilogue rotates and splits into heads; small batches (the draft model's) take the narrow
     // GEMM, whose 64-column tiles do not hold a whole head, and rotate in a kernel of their own
     const bool fused_rope = bf && Dh == 128 && n > 128;
-    if (fused_rope) {
+    if (q4) {  // at most 128 rows: the three 4-bit projections stacked in one launch, rotation in its own kernel
+      const sx_w4_matrix mats[3] = {q4->wq, q4->wk, q4->wv};
+      const int ns[3] = {Nq, Nkv, Nkv};
+      SX_TIMED(SX_K_GEMM_QKV, sx_launch_gemm_w4_regs(L.x, mats, ns, 3, w->w4_group, L.qkv, Nq + 2 * Nkv, n, d,
+                                                     SX_GEMM_STORE, split_ws, split_bytes, st));
+    } else if (fused_rope) {
       SX_TIMED(SX_K_GEMM_QKV,
                sx_launch_gemm_qkv_rope_bf16(L.x, lw.wq, lw.wk, lw.wv, Hq, Hkv, rope_cs, L.q, tk, tv, n, d, split_ws,
                                             split_bytes, st));
@@ -192,6 +257,18 @@ int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const v
     if (bf) {
       SX_TIMED(SX_K_ATTN, sx_launch_tree_attn_bf16(L.q, tkb, tvb, pk, pv, L.klist, L.kcnt, L.rowmask, T, n, P, Hq, Hkv,
                                                    L.o, n <= 128 ? L.attn_split_ws : nullptr, L.attn_split_bytes, st));
+      if (q4) {
+        const int one_d[1] = {d}, two_f[2] = {F, F};
+        const sx_w4_matrix gu[2] = {q4->w_gate, q4->w_up};
+        SX_TIMED(SX_K_GEMM_O, sx_launch_gemm_w4_regs(L.o, &q4->wo, one_d, 1, w->w4_group, L.h, d, n, Nq, SX_GEMM_RESIDUAL,
+                                                     split_ws, split_bytes, st));
+        SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
+        SX_TIMED(SX_K_GEMM_GATEUP, sx_launch_gemm_w4_regs(L.x, gu, two_f, 2, w->w4_group, L.gu, 2 * F, n, d, SX_GEMM_STORE,
+                                                          split_ws, split_bytes, st));
+        SX_TIMED(SX_K_GEMM_GATEUP, sx_launch_swiglu_pair_bf16(L.gu, n, F, L.act, st));
+        SX_TIMED(SX_K_GEMM_DOWN, sx_launch_gemm_w4_regs(L.act, &q4->w_down, one_d, 1, w->w4_group, L.h, d, n, F,
+                                                        SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
+      } else {
       SX_TIMED(SX_K_GEMM_O,
                sx_launch_gemm_bf16(L.o, lw.wo, nullptr, nullptr, d, 0, 0, L.h, n, Nq, SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
       SX_TIMED(SX_K_NORM, sx_launch_rmsnorm(L.h, lw.ffn_norm, c.dtype, n, d, c.rms_eps, L.x, st));
@@ -199,6 +276,7 @@ int sx_verify_tree_range_impl(const sx_weights* w, const void* prefix_k, const v
                sx_launch_gemm_bf16(L.x, lw.w_gate, lw.w_up, nullptr, F, F, 0, L.act, n, d, SX_GEMM_SWIGLU, split_ws, split_bytes, st));
       SX_TIMED(SX_K_GEMM_DOWN,
                sx_launch_gemm_bf16(L.act, lw.w_down, nullptr, nullptr, d, 0, 0, L.h, n, F, SX_GEMM_RESIDUAL, split_ws, split_bytes, st));
+      }
     } else {
       SX_TRY(sx_launch_tree_attn_f32((const float*)L.q, (const float*)tkb, (const float*)tvb, (const float*)pk,
                                      (const float*)pv, L.par_s, L.depth, T, first, P, Hq, Hkv, Dh, (float*)L.o, st));

@@ -365,7 +365,9 @@ def test_gemm_bf16_llama3_vocabulary_head(sx, M):
 
 @pytest.mark.parametrize("M,N,K,group,split", [(128, 4096, 4096, 128, True), (128, 256, 11008, 64, True),
                                                (37, 200, 256, 128, False), (1, 64, 64, 64, False),
-                                               (100, 12288, 512, 128, True)])
+                                               (100, 12288, 512, 128, True), (128, 300, 128, 64, False),
+                                               (5, 1000, 1024, 256, True), (128, 520, 2048, 1024, True),
+                                               (64, 768, 192, 64, True)])
 def test_gemm_w4a16(sx, M, N, K, group, split):
     """4-bit group-quantised weights dequantised in registers: against the oracle's product with the weights it
     dequantises by the stated formula (bf16(scale * (code - zero))); with and without K cut among workgroups,

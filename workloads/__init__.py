@@ -10,6 +10,6 @@ tree is a legal one); no expected value of a test comes from it.
 """
 from .gen import (  # noqa: F401
     ModelCfg, CONFIGS, hash_normal, gen_weights, gen_layer, gen_model_ends, gen_prefix_kv, gen_tokens,
-    gen_uniform_tree, gen_best_first_tree, gen_chain_tree, gen_expand_inputs, gen_w4,
+    gen_uniform_tree, gen_best_first_tree, gen_chain_tree, gen_expand_inputs, gen_w4, gen_w4_layers,
     gen_crafted_logits, tree_stats,
 )

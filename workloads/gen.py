@@ -339,3 +339,22 @@ def gen_w4(N: int, K: int, group: int, seed: int):
     scales = torch.from_numpy(r.uniform(0.002, 0.02, size=(N, K // group)).astype(np.float32)).to(torch.bfloat16)
     zeros = torch.from_numpy(r.integers(0, 16, size=(N, K // group), dtype=np.int64).astype(np.uint8))
     return torch.from_numpy(qweight.view(np.int32)), scales, zeros
+
+
+def gen_w4_layers(cfg: ModelCfg, group: int, seed: int, device="cpu", scale: float = 0.3) -> list:
+    """Random 4-bit decoder layers for a whole model, made on `device` with torch's generator (the 7B-shaped draft
+    model holds 6.5 G codes: too many for the numpy stream of gen_w4 in reasonable time): per layer a dict name ->
+    (qweight int32 [N][K/8], scales bf16 [N][K/group] in scale * (0.002 .. 0.02), zeros uint8 [N][K/group] in 0..15)."""
+    g = torch.Generator(device=device).manual_seed(seed)
+    shapes = layer_shapes(cfg)
+    layers = []
+    for _ in range(cfg.n_layers):
+        lq = {}
+        for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            N, K = shapes[name]
+            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, K // 8), dtype=torch.int32, device=device, generator=g)
+            sc = ((torch.rand((N, K // group), device=device, generator=g) * 0.018 + 0.002) * scale).to(torch.bfloat16)
+            zr = torch.randint(0, 16, (N, K // group), dtype=torch.uint8, device=device, generator=g)
+            lq[name] = (qw, sc, zr)
+        layers.append(lq)
+    return layers
