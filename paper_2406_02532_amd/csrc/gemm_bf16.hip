@@ -292,6 +292,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     pfx = __builtin_amdgcn_raw_buffer_load_b32(xres, pfxoff, pso, 0);                                          \
     pfw = __builtin_amdgcn_raw_buffer_load_b32(pfwres, pfwoff, pso, 0);                                        \
   }
+#ifndef SX_SPLIT_BATCH
+#define SX_SPLIT_BATCH 16
+#endif
 #ifndef SX_COPY_ROWS
 #define SX_COPY_ROWS 8
 #endif
@@ -361,29 +364,31 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     }
     __syncthreads();
     if (!s_last) return;
-    // Read back in batches of 16 blocks per part, all loads of a batch in flight together: one memory round
+    constexpr int kBatch = SX_SPLIT_BATCH;
+    // Read back in batches of kBatch blocks per part, all loads of a batch in flight together: one memory round
     // trip per batch and part instead of one per block (a block at a time, the 64 dependent round trips were
     // most of what the split cost).  Parts are added in part order whatever the batch size.
     const unsigned all = (unsigned)((tail_tile * ksplit * 4 + wave) * (64 * 256) + lane * 4) * 4u;
 #pragma unroll
-    for (int b0 = 0; b0 < 64; b0 += 16) {
-      f32x4 sum[16];
+    for (int b0 = 0; b0 < 64; b0 += kBatch) {
+      f32x4 sum[kBatch];
+      for (int p = 0; p < ksplit; ++p) {
+        f32x4 t[kBatch];
+        if (p == kpart) {  // this workgroup's own part is still in its registers (the same bits it stored)
 #pragma unroll
-      for (int b = 0; b < 16; ++b)
-        sum[b] = __builtin_bit_cast(
-            f32x4, __builtin_amdgcn_raw_buffer_load_b128(pres, all + (b0 + b) * 1024, 0, kScopeDevice));
-      for (int p = 1; p < ksplit; ++p) {
-        f32x4 t[16];
+          for (int b = 0; b < kBatch; ++b) t[b] = acc[(b0 + b) >> 3][(b0 + b) & 7];
+        } else {
 #pragma unroll
-        for (int b = 0; b < 16; ++b)
-          t[b] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                                               pres, all + (unsigned)p * (4u * 64 * 256 * 4) + (b0 + b) * 1024, 0,
-                                               kScopeDevice));
+          for (int b = 0; b < kBatch; ++b)
+            t[b] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 pres, all + (unsigned)p * (4u * 64 * 256 * 4) + (b0 + b) * 1024, 0,
+                                                 kScopeDevice));
+        }
 #pragma unroll
-        for (int b = 0; b < 16; ++b) sum[b] += t[b];
+        for (int b = 0; b < kBatch; ++b) sum[b] = p == 0 ? t[b] : sum[b] + t[b];
       }
 #pragma unroll
-      for (int b = 0; b < 16; ++b) acc[(b0 + b) >> 3][(b0 + b) & 7] = sum[b];
+      for (int b = 0; b < kBatch; ++b) acc[(b0 + b) >> 3][(b0 + b) & 7] = sum[b];
     }
   }
 
@@ -497,7 +502,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 
 // Decides whether the last tiles get a K split: only when there are more tiles than compute units with a
 // remainder that would fill at most half of the chip for a whole round, and the caller gave memory for the
-// partial sums; 2 ways, parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
+// partial sums; up to 4 ways (as many as it takes to give every compute unit a part), parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
 // small M, the draft model's batches -- was measured too: the partial sums, 256 KB per part, then outweigh
 // the weights being streamed, and the launch gets slower; such shapes want narrower tiles, not a K split.)
 void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
@@ -510,7 +515,7 @@ void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   const int rest = tiles % cus;
   if (rest == 0 || 2 * rest > cus) return;
   int split = cus / rest;
-  if (split > 2) split = 2;  // measured at the 70B QKV shape: 2 ways 325 us, 3 ways 338, 4 ways 335 (uncut: 372)
+  if (split > 4) split = 4;  // measured at the 70B QKV shape: 4 ways 289 us, 3 ways 295, 2 ways 313 (uncut: 372)
   while (split > 1 && nb / split < 8) --split;
   if (split < 2 || rest > 256) return;
   if (split_ws_bytes < 1024 + (size_t)rest * split * BM * BN * sizeof(float)) return;
