@@ -321,6 +321,15 @@ int sx_row_logsoftmax_topk(const float *logits, int32_t N, int32_t V, int32_t k,
  * bf16(silu(X W^T) * (X W2^T)) (SwiGLU).  W2 is ignored in modes 0 and 1. */
 int sx_gemm_bf16(const void *X, const void *W, const void *W2, void *Y, int32_t M, int32_t N,
                  int32_t K, int32_t mode, void *stream);
+/* The same product with memory for partial sums, as the forward calls it: where the output tiles (256 x 256)
+ * are fewer than half the compute units, or their last round would fill at most half of them, those tiles
+ * are cut along K among several workgroups; the parts are added in a fixed order, so results repeat bit for
+ * bit.  workspace: NULL (then exactly sx_gemm_bf16), or device memory of sx_gemm_bf16_workspace() bytes,
+ * 256-byte aligned (SX_ERR_WORKSPACE otherwise), whose first 1024 bytes are zero before the first call (every call
+ * leaves them zero); caller-owned; calls that share a workspace must not overlap. */
+size_t sx_gemm_bf16_workspace(void);
+int sx_gemm_bf16_ws(const void *X, const void *W, const void *W2, void *Y, int32_t M, int32_t N,
+                    int32_t K, int32_t mode, void *workspace, size_t workspace_bytes, void *stream);
 
 /* QKV projection of the decoder layer (Alg. 1, FORWARD) with the rotary embedding applied in the
  * GEMM's epilogue, head_dim 128: q_out device bf16 [T][n_q_heads][128], k_out and v_out device

@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecexec
 EXPORTS = ["sx_verify_tree_workspace", "sx_verify_tree_w4_workspace", "sx_verify_tree", "sx_verify_tree_cached", "sx_verify_tree_range", "sx_commit_kv",
            "sx_specexec_round_workspace", "sx_specexec_round", "sx_draft_tree_workspace", "sx_draft_tree", "sx_accept_walk_workspace", "sx_accept_walk",
            "sx_expand_topk_workspace", "sx_expand_topk", "sx_expand_topk_static", "sx_check_status", "sx_status_string", "sx_version",
-           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_gemm_w4a16_workspace", "sx_gemm_w4a16_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
+           "sx_row_logsoftmax_topk", "sx_gemm_bf16", "sx_gemm_bf16_workspace", "sx_gemm_bf16_ws", "sx_gemm_w4a16_workspace", "sx_gemm_w4a16_bf16", "sx_qkv_rope_workspace", "sx_qkv_rope_bf16", "sx_tree_attention_workspace", "sx_tree_attention_bf16",
            "sx_profile_enable", "sx_profile_select", "sx_profile_disable", "sx_profile_read"]
 
 SX_F32, SX_BF16 = 0, 1
@@ -97,6 +97,10 @@ def _load():
     L.sx_row_logsoftmax_topk.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     L.sx_gemm_bf16.restype = C.c_int
     L.sx_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.sx_gemm_bf16_workspace.restype = sz
+    L.sx_gemm_bf16_workspace.argtypes = []
+    L.sx_gemm_bf16_ws.restype = C.c_int
+    L.sx_gemm_bf16_ws.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     L.sx_gemm_w4a16_workspace.restype = sz
     L.sx_gemm_w4a16_workspace.argtypes = []
     L.sx_gemm_w4a16_bf16.restype = C.c_int
@@ -363,11 +367,16 @@ def row_logsoftmax_topk(logits, k: int, topk_logp=None, topk_idx=None, stream=No
     return topk_logp, topk_idx
 
 
-def gemm_bf16(X, W, Y, mode: int = 0, W2=None, stream=None):
-    """sx_gemm_bf16: Y = X W^T (mode 0), Y += X W^T (mode 1), Y = bf16(silu(X W^T) * (X W2^T)) (mode 2)."""
+def gemm_bf16(X, W, Y, mode: int = 0, W2=None, workspace=None, stream=None):
+    """sx_gemm_bf16 / sx_gemm_bf16_ws: Y = X W^T (mode 0), Y += X W^T (mode 1), Y = bf16(silu(X W^T) * (X W2^T))
+    (mode 2).  workspace: a uint8 tensor of sx_gemm_bf16_workspace() bytes, zero before its first use."""
     M, K = X.shape
     N = W.shape[0]
-    _check(lib.sx_gemm_bf16(_ptr(X), _ptr(W), _ptr(W2), _ptr(Y), M, N, K, mode, _stream(stream)), "sx_gemm_bf16")
+    if workspace is None:
+        _check(lib.sx_gemm_bf16(_ptr(X), _ptr(W), _ptr(W2), _ptr(Y), M, N, K, mode, _stream(stream)), "sx_gemm_bf16")
+    else:
+        _check(lib.sx_gemm_bf16_ws(_ptr(X), _ptr(W), _ptr(W2), _ptr(Y), M, N, K, mode, _ptr(workspace),
+                                   workspace.numel(), _stream(stream)), "sx_gemm_bf16_ws")
     return Y
 
 

@@ -175,7 +175,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   // is read by 4 of them and a W tile by 8, at about the same time, so all of them wait for the one
   // fabric access.  Instead each touches its share of the lines (X: 64 rows = 16 per wave; W: 32 rows
   // = 8 per wave; one dword per 128-byte line) kPfDist slabs ahead, and the copies of all of them find
-  // the lines in L2.  Measured at the 70B shapes: QKV +12%, gate/up +4%, down +6%, O -3%.
+  // the lines in L2.  Measured at the 70B shapes: QKV +12%, gate/up +4%, down +6%, O -3%.  (Where nobody shares --
+  // other tile counts -- a workgroup touching all of its own lines ahead of its copies was measured too: 5 to 20%
+  // slower at every shape and distance; the copies are not waiting for HBM latency there.)
   int pfx = 0, pfw = 0, pfxoff = 0, pfwoff = 0;
   __amdgpu_buffer_rsrc_t pfwres = wres0;
   if (PF) {
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   }                                                                                                            \
   if (PF) { /* youngest in the queue: the barrier's wait lets these two loads stay in flight */                \
     asm volatile("" ::"v"(pfx), "v"(pfw));                                                                     \
-    const int pso = min((SO_) + kPfDist * (BK * 2), last * (BK * 2));                                          \
+    const int pso = min((SO_) + kPfDist * (BK * 2), last * (BK * 2));                 \
     pfx = __builtin_amdgcn_raw_buffer_load_b32(xres, pfxoff, pso, 0);                                          \
     pfw = __builtin_amdgcn_raw_buffer_load_b32(pfwres, pfwoff, pso, 0);                                        \
   }
@@ -500,18 +502,47 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #undef SX_WAIT_BARRIER
 
 
-// Decides whether the last tiles get a K split: only when there are more tiles than compute units with a
-// remainder that would fill at most half of the chip for a whole round, and the caller gave memory for the
-// partial sums; up to 4 ways (as many as it takes to give every compute unit a part), parts of at least 8 slabs.  (Cutting every tile of a launch with few tiles --
-// small M, the draft model's batches -- was measured too: the partial sums, 256 KB per part, then outweigh
-// the weights being streamed, and the launch gets slower; such shapes want narrower tiles, not a K split.)
+// Decides which tiles are cut along K, given memory for the partial sums.  More tiles than compute units with a
+// remainder that would fill at most half of the chip for a whole round: the remainder tiles, up to 4 ways (as many
+// as it takes to give every compute unit a part).  Fewer tiles than half the compute units: all of them.  Parts
+// are at least 8 slabs long.  (Batches of at most 128 rows never come here: for them a partial tile of 256 KB
+// outweighs the weights a part streams, and they take the narrow-tile kernel instead.)
+constexpr float kSplitPerPartSlabs = 4.5f;
+constexpr int kSplitMaxWays = 16;
 void plan_split(GemmArgs& a, void* split_ws, size_t split_ws_bytes) {
   a.split = 1;
   a.part = nullptr;
   a.part_cnt = nullptr;
   a.full_tiles = a.tail_items = a.full_per_xcd = a.tail_per_xcd = 0;
   const int cus = sx_compute_units(), tiles = a.tilesM * a.tilesN, nb = a.K / BK;
-  if (!split_ws || tiles <= cus) return;
+  if (!split_ws) return;
+  if (2 * tiles <= cus) {
+    // Fewer tiles than half the compute units (trees of a few hundred nodes, narrow models): every tile is cut, as
+    // many ways as keeps all parts in one round and pays.  Cost of a cut in slab times: each part walks nb / s
+    // slabs, and every further way costs about 4.5 (a partial tile written, and read back by the last arriver) --
+    // fitted to sweeps at the 70B and 7B layer shapes for 256 to 1024 rows, where it picks the fastest or
+    // second-fastest cut (e.g. 8192 x 8192 at 256 rows: 152 us uncut, 74 us cut 5 ways, 82 us cut 8 ways).
+    int best = 1;
+    float best_cost = (float)nb + kSplitPerPartSlabs;
+    for (int s2 = 2; s2 * tiles <= cus && s2 <= kSplitMaxWays && nb / s2 >= 8; ++s2) {
+      const float cost = (float)nb / s2 + kSplitPerPartSlabs * s2;
+      if (cost < best_cost) {
+        best_cost = cost;
+        best = s2;
+      }
+    }
+    if (best < 2 || tiles > 256) return;
+    if (split_ws_bytes < 1024 + (size_t)tiles * best * BM * BN * sizeof(float)) return;
+    a.split = best;
+    a.full_tiles = 0;
+    a.tail_items = tiles * best;
+    a.full_per_xcd = 0;
+    a.tail_per_xcd = (a.tail_items + 7) / 8;
+    a.part_cnt = static_cast<int*>(split_ws);
+    a.part = reinterpret_cast<float*>(static_cast<char*>(split_ws) + 1024);
+    return;
+  }
+  if (tiles <= cus) return;
   const int rest = tiles % cus;
   if (rest == 0 || 2 * rest > cus) return;
   int split = cus / rest;
@@ -615,11 +646,20 @@ int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, 
   return launch<SX_GEMM_QKV_ROPE>(a, st);
 }
 
-extern "C" int sx_gemm_bf16(const void* X, const void* W, const void* W2, void* Y, int32_t M, int32_t N, int32_t K,
-                            int32_t mode, void* stream) {
+extern "C" size_t sx_gemm_bf16_workspace(void) { return sx_gemm_split_workspace(); }
+
+extern "C" int sx_gemm_bf16_ws(const void* X, const void* W, const void* W2, void* Y, int32_t M, int32_t N, int32_t K,
+                               int32_t mode, void* workspace, size_t workspace_bytes, void* stream) {
   if (!X || !W || !Y || (mode == SX_GEMM_SWIGLU && !W2)) return SX_ERR_NULL;
   if (mode < 0 || mode > 2 || N < 1) return SX_ERR_SHAPE;
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255)) return SX_ERR_WORKSPACE;
   if (mode == SX_GEMM_SWIGLU)
-    return sx_launch_gemm_bf16(X, W, W2, nullptr, N, N, 0, Y, M, K, mode, nullptr, 0, (hipStream_t)stream);
-  return sx_launch_gemm_bf16(X, W, nullptr, nullptr, N, 0, 0, Y, M, K, mode, nullptr, 0, (hipStream_t)stream);
+    return sx_launch_gemm_bf16(X, W, W2, nullptr, N, N, 0, Y, M, K, mode, workspace, workspace_bytes, (hipStream_t)stream);
+  return sx_launch_gemm_bf16(X, W, nullptr, nullptr, N, 0, 0, Y, M, K, mode, workspace, workspace_bytes,
+                             (hipStream_t)stream);
+}
+
+extern "C" int sx_gemm_bf16(const void* X, const void* W, const void* W2, void* Y, int32_t M, int32_t N, int32_t K,
+                            int32_t mode, void* stream) {
+  return sx_gemm_bf16_ws(X, W, W2, Y, M, N, K, mode, nullptr, 0, stream);
 }

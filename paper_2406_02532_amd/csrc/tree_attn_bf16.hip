@@ -70,6 +70,22 @@ __device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_
   return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
+#ifdef SX_ATT_NO_SB
+#define SX_ATT_SCHED_BARRIER
+#else
+#define SX_ATT_SCHED_BARRIER __builtin_amdgcn_sched_barrier(0);
+#endif
+// maximum of a value over the lane pair (l, l ^ 32): one lane-half swap inside the vector unit, no LDS round trip
+__device__ __forceinline__ float pair_max(float x) {
+#ifdef SX_ATT_BPERMUTE
+  return fmaxf(x, __shfl_xor(x, 32, 64));
+#else
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+#endif
+}
+#define SX_ATT_XMAX(x) pair_max(x)
 // s_waitcnt: all vector-memory operations (the copies) and all LDS reads of this wave done
 constexpr int kWaitAll = 0x0070;
 // The barrier intrinsic does not order memory operations for the compiler, and a workgroup fence would be
@@ -91,7 +107,18 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lh = lane >> 5;
-  const int tile = blockIdx.x, kvh = blockIdx.y;
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  With a multiple of 8 KV heads
+  // every XCD takes the heads congruent to its number, one after the other, all query tiles of a head
+  // before the next: the K/V rows of a head are then fetched into one L2 only, and the workgroups that
+  // run there side by side all read them.
+  int tile = blockIdx.x, kvh = blockIdx.y;
+#ifndef SX_ATT_NO_XCD
+  if ((gridDim.y & 7) == 0) {
+    const int lin = blockIdx.x + gridDim.x * blockIdx.y, j = lin >> 3;
+    tile = j % gridDim.x;
+    kvh = ((j / gridDim.x) << 3) + (lin & 7);
+  }
+#endif
   const int n0 = tile * a.npt;
 
   // ---- this lane's query row -----------------------------------------------------------------------
@@ -189,11 +216,18 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   {                                                                                                                \
     /* ---- S^T = K Q^T : st[kb][e] = score(key 32kb + 8(e/4) + 4lh + e%4, this lane's row) ---- */               \
     f32x16 st[2];                                                                                                  \
-    _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                             \
-      _Pragma("unroll") for (int e = 0; e < 16; ++e) st[kb][e] = 0.f;                                              \
+    {                                                                                                              \
+      /* all 16 fragment reads go out before the first MFMA: one LDS latency per tile instead of one per MFMA */   \
+      bf16x8 kfa[8], kfb[8];                                                                                       \
+      _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)                                                             \
+          kfa[ks] = *reinterpret_cast<const bf16x8*>(KS_ + ks_off(l32, 2 * ks + lh));                              \
+      _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)                                                             \
+          kfb[ks] = *reinterpret_cast<const bf16x8*>(KS_ + ks_off(32 + l32, 2 * ks + lh));                         \
+      SX_ATT_SCHED_BARRIER                                                                                         \
+      _Pragma("unroll") for (int e = 0; e < 16; ++e) st[0][e] = st[1][e] = 0.f;                                    \
       _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {                                                           \
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(KS_ + ks_off(32 * kb + l32, 2 * ks + lh));              \
-        st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);                             \
+        st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa[ks], qf[ks], st[0], 0, 0, 0);                          \
+        st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfb[ks], qf[ks], st[1], 0, 0, 0);                          \
       }                                                                                                            \
     }                                                                                                              \
     /* ---- online softmax for this row ---- */                                                                    \
@@ -206,7 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
     }                                                                                                              \
     _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int e = 0; e < 16; ++e)                \
         mx = fmaxf(mx, st[kb][e]);                                                                                 \
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                        \
+    mx = SX_ATT_XMAX(mx);                                                                                          \
     float alpha = 1.0f;                                                                                            \
     if (mx > m_ref + slack_raw) { /* also taken on the first tile (m_ref = -inf) */                                \
       alpha = __builtin_amdgcn_exp2f((m_ref - mx) * c2);                                                           \

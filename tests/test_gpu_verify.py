@@ -402,6 +402,46 @@ def test_gemm_bf16_swiglu(sx, M, F, K):
     assert np.all(np.abs(got - ref) <= 0.51 * bf16_ulp(ref) + 1e-5 * np.abs(ref).max())   # correctly rounded up to fp32 noise
 
 
+@pytest.mark.parametrize("M,N,K,mode", [(256, 2048, 4096, 0), (256, 2048, 4096, 1), (200, 1000, 2048, 1),
+                                        (1024, 8192, 1024, 1), (300, 2100, 1536, 0), (256, 1024, 11008, 1),
+                                        (256, 1536, 2048, 2), (200, 1000, 1024, 2)])
+def test_gemm_bf16_few_tiles_cut_along_k(sx, M, N, K, mode):
+    """Launches whose 256 x 256 output tiles are fewer than half the compute units (trees of a few hundred nodes):
+    with a workspace every tile is cut along K among several workgroups.  All three epilogues against the fp64
+    product, ragged edges, and bit-identical repeats (the parts are added in part order whoever arrives last)."""
+    X = wl.hash_normal(41, (M, K), dtype=torch.bfloat16)
+    W = wl.hash_normal(42, (N, K), std=0.05, dtype=torch.bfloat16)
+    W2 = wl.hash_normal(43, (N, K), std=0.05, dtype=torch.bfloat16) if mode == 2 else None
+    ws = torch.zeros(sx.lib.sx_gemm_bf16_workspace(), dtype=torch.uint8, device=dev())
+    Xd, Wd, W2d = X.to(dev()), W.to(dev()), None if W2 is None else W2.to(dev())
+    ref = X.double().numpy() @ W.double().numpy().T
+    outs = []
+    for rep in range(3):
+        if mode == 2:
+            Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+        else:
+            Y = torch.full((M, N), 0.5, dtype=torch.float32, device=dev())
+        sx.gemm_bf16(Xd, Wd, Y, mode=mode, W2=W2d, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(Y.cpu())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert int(ws[:1024].max()) == 0                                          # the counters are back at zero
+    got = outs[0].double().numpy()
+    if mode == 2:
+        u = X.double().numpy() @ W2.double().numpy().T
+        want = ref / (1 + np.exp(-ref)) * u
+        assert np.all(np.abs(got - want) <= 0.51 * bf16_ulp(want) + 1e-5 * np.abs(want).max())
+    else:
+        want = ref + 0.5 if mode == 1 else ref
+        assert np.abs(got - want).max() <= 1e-5 * np.sqrt(K) * np.abs(ref).max() + 1e-6
+    # and the same call without a workspace (no cut) agrees to fp32 summation-order noise
+    Y0 = torch.zeros((M, N), dtype=torch.bfloat16 if mode == 2 else torch.float32, device=dev())
+    sx.gemm_bf16(Xd, Wd, Y0, mode=mode, W2=W2d)
+    torch.cuda.synchronize()
+    d = np.abs(Y0.cpu().double().numpy() - (got - (0.5 if mode == 1 else 0.0)))
+    assert d.max() <= (1.01 * bf16_ulp(got).max() if mode == 2 else 1e-5 * np.sqrt(K) * np.abs(ref).max() + 1e-6)
+
+
 # the last three shapes give more output tiles than the chip has compute units with a small remainder: the
 # remainder tiles are cut along K and their partial sums added up by the last workgroup to arrive
 @pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2),
