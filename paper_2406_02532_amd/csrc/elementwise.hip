@@ -125,7 +125,7 @@ __global__ void swiglu_pair_bf16_kernel(const float* __restrict__ gu, int n, int
   if (idx >= (size_t)n * F) return;
   const size_t i = idx / F, f = idx % F;
   const float g = gu[i * 2 * F + f], u = gu[i * 2 * F + F + f];
-  act[idx] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
+  act[idx] = (unsigned short)f32_to_bf16_bits(silu_mul_bf16_bound(g, u));
 }
 
 // One 32-bit word of eight 4-bit codes per thread -> eight bf16 weights w = bf16(scale * (code - zero)) (16 bytes).

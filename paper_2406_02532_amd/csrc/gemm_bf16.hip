@@ -458,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float g = acc[2 * ii][j][e], u = acc[2 * ii + 1][j][e];
-          h[e] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
+          h[e] = (unsigned short)f32_to_bf16_bits(silu_mul_bf16_bound(g, u));
         }
         unsigned short* y = Y + (size_t)m * a.N + f;
         if (vec) {
@@ -472,6 +472,30 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
             if (f + e < a.N) y[e] = h[e];
         }
       }
+    }
+  } else if (vec && tile_m * BM + BM <= a.M && tile_n * BN + BN <= a.N) {
+    // A whole tile: no edge tests, and the residual comes in 16 loads at a time (two row blocks) before the first
+    // add -- a load, an add and a store per block, each waiting for its own load, made the epilogue 64 memory
+    // round trips long.
+    float* Yb = static_cast<float*>(a.Y) + (size_t)(mbase + l16) * a.N + (tile_n * BN + wn * 128 + 4 * lq);
+#pragma unroll
+    for (int j0 = 0; j0 < 8; j0 += 2) {
+      f32x4 r[2][8];
+      if (MODE == SX_GEMM_RESIDUAL) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            r[jj][i] = *reinterpret_cast<const f32x4*>(Yb + (size_t)(16 * (j0 + jj)) * a.N + 16 * i);
+      }
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          f32x4 v = acc[i][j0 + jj];
+          if (MODE == SX_GEMM_RESIDUAL) v += r[jj][i];
+          *reinterpret_cast<f32x4*>(Yb + (size_t)(16 * (j0 + jj)) * a.N + 16 * i) = v;
+        }
     }
   } else {
     float* Y = static_cast<float*>(a.Y);

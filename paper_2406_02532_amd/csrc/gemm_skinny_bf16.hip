@@ -6,6 +6,12 @@
 // LDS by buffer loads that write LDS (whole 128-byte lines, chunk swizzle applied on the global side), three
 // stages of K = 64, one barrier per stage, v_mfma_f32_16x16x32_bf16 with the product formed transposed so that
 // a lane holds 4 consecutive output columns.
+//
+// What bounds it (7B shapes, 128 rows): 2.0-2.3 TB/s of weights from HBM, 3.3-4.2 TB/s out of the Infinity Cache.
+// A plain load kernel walking the same 64 rows x 128 bytes per step streams the same matrix from HBM at 5 TB/s,
+// and a fifth wave touching the weight lines 3 to 12 slabs ahead of the copies made every shape slower: the
+// weights are not what the copies wait for.  Every tile copies all 128 rows of X again (16 KB per slab next to
+// 8 KB of weights), so the L2 -> LDS stream carries three times the weight bytes, with two slabs of lookahead.
 #include "kernels.h"
 
 namespace {
@@ -205,7 +211,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float g = acc[0][j][e], u = acc[1][j][e];
-        h[e] = (unsigned short)f32_to_bf16_bits(g / (1.0f + expf(-g)) * u);
+        h[e] = (unsigned short)f32_to_bf16_bits(silu_mul_bf16_bound(g, u));
       }
       unsigned short* y = Y + (size_t)m * a.N + f;
       if (vec) {
