@@ -402,6 +402,11 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     // the same for the whole wave.  Column 16 i + 4 lq + e and column + 64 (block i + 4, same lane and
     // register) are the pair the rotary embedding turns by the row's angle (Alg. 1: node at position
     // P + depth); the values are rounded to bf16 once, after the rotation.
+    // (The table loads of a row block sit behind the stores of the one before, so every row block waits for a
+    // memory round trip.  Requesting them a row block ahead in a second set of 32 registers was tried: the tiles
+    // that come out of the K-split reduction then gave different bits from run to run -- cause not found, the
+    // registers of this kernel are all in use at that point -- and the change was taken out again;
+    // tests/test_gpu_verify.py repeats this projection in fresh workspaces to guard the property.)
     const int head = tile_n * 2 + wn;
     const bool is_v = head >= a.hq + a.hkv;
     unsigned short* dst = head < a.hq ? a.q : is_v ? a.v : a.k;

@@ -183,19 +183,26 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
     }
     __syncthreads();
     if (!s_last) return;
+    // all 8 blocks of a part are requested together (one memory round trip per part, not one per block); the
+    // workgroup's own part comes from its registers (the same bits it stored); parts are added in part order
     const unsigned all = (unsigned)(tile_n * a.split * kPartFloats + wave * (8 * 256) + lane * 4) * 4u;
+    f32x4 sum[8];
+    for (int p = 0; p < a.split; ++p) {
+      f32x4 t[8];
+      if (p == kpart) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int b = 0; b < 8; ++b) t[b] = acc[b >> 2][b & 3];
+      } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 sum = __builtin_bit_cast(
-            f32x4, __builtin_amdgcn_raw_buffer_load_b128(pres, all + (i * 4 + j) * 1024, 0, kScopeDevice));
-        for (int p = 1; p < a.split; ++p)
-          sum += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                                               pres, all + (unsigned)p * (kPartFloats * 4u) + (i * 4 + j) * 1024, 0,
-                                               kScopeDevice));
-        acc[i][j] = sum;
+        for (int b = 0; b < 8; ++b)
+          t[b] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                               pres, all + (unsigned)p * (kPartFloats * 4u) + b * 1024, 0, kScopeDevice));
       }
+#pragma unroll
+      for (int b = 0; b < 8; ++b) sum[b] = p == 0 ? t[b] : sum[b] + t[b];
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[b >> 2][b & 3] = sum[b];
   }
 
   // ---- epilogue.  acc[i][j][e]: output row 64 wm + 16 j + l16, W row 32 wn + 16 i + 4 lq + e ------------------
@@ -223,6 +230,29 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if (f + e < a.N) y[e] = h[e];
+      }
+    }
+  } else if (vec && tile_n * BN + BN <= a.N) {
+    // whole column tile: the residual of all 8 blocks is requested before the first add (rows past M read row M - 1
+    // and store nothing); block by block the epilogue was 8 memory round trips long
+    float* Yb = static_cast<float*>(a.Y) + (tile_n * BN + wn * 32 + 4 * lq);
+    f32x4 r[4][2];
+    if (MODE == SX_GEMM_RESIDUAL) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          r[j][i] = *reinterpret_cast<const f32x4*>(Yb + (size_t)min(wm * 64 + 16 * j + l16, a.M - 1) * a.N + 16 * i);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = wm * 64 + 16 * j + l16;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        f32x4 v = acc[i][j];
+        if (MODE == SX_GEMM_RESIDUAL) v += r[j][i];
+        *reinterpret_cast<f32x4*>(Yb + (size_t)m * a.N + 16 * i) = v;
       }
     }
   } else {

@@ -466,6 +466,28 @@ def test_qkv_projection_with_rotary_epilogue(sx, T, d, Hq, Hkv):
         assert np.all(np.abs(got - ref) <= 0.51 * bf16_ulp(ref) + 2e-5 * np.abs(ref).max())
 
 
+def test_qkv_projection_repeats_bit_for_bit_in_fresh_workspaces(sx):
+    """The tail tiles of this shape (320 tiles on 256 compute units, the last 64 cut four ways along K) take their
+    partial sums through memory: four calls, each in a workspace of its own holding whatever was there before, give
+    the same bits."""
+    T, d, Hq, Hkv = 2048, 2048, 64, 8
+    X = wl.hash_normal(11, (T, d), dtype=torch.bfloat16).to(dev())
+    Wq = wl.hash_normal(12, (Hq * 128, d), std=0.05, dtype=torch.bfloat16).to(dev())
+    Wk = wl.hash_normal(13, (Hkv * 128, d), std=0.05, dtype=torch.bfloat16).to(dev())
+    Wv = wl.hash_normal(14, (Hkv * 128, d), std=0.05, dtype=torch.bfloat16).to(dev())
+    pos = torch.arange(T, dtype=torch.int32, device=dev()) + 5
+    outs = []
+    for r in range(4):
+        junk = torch.full((1 << 25,), 0.3 + 1.7 * r, device=dev())      # what the next workspace is carved from
+        del junk
+        q, k, v = sx.qkv_rope_bf16(X, Wq, Wk, Wv, pos, 10000.0)
+        torch.cuda.synchronize()
+        outs.append((q.clone(), k.clone(), v.clone()))
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
 def _attn_case(sx, T, P, Hq, Hkv, tree, seed):
     tok, par = tree
     q = wl.hash_normal(seed, (T, Hq, 128), std=1.5, dtype=torch.bfloat16)
