@@ -7,21 +7,26 @@
 // stages of K = 64, one barrier per stage, v_mfma_f32_16x16x32_bf16 with the product formed transposed so that
 // a lane holds 4 consecutive output columns.
 //
-// What bounds it (7B shapes, 128 rows): 2.0-2.3 TB/s of weights from HBM, 3.3-4.2 TB/s out of the Infinity Cache.
+// What bounds it (7B shapes, 128 rows): 2.0-2.4 TB/s of weights from HBM, 3-6 TB/s out of the Infinity Cache.
 // A plain load kernel walking the same 64 rows x 128 bytes per step streams the same matrix from HBM at 5 TB/s,
-// and a fifth wave touching the weight lines 3 to 12 slabs ahead of the copies made every shape slower: the
-// weights are not what the copies wait for.  Every tile copies all 128 rows of X again (16 KB per slab next to
-// 8 KB of weights), so the L2 -> LDS stream carries three times the weight bytes, with two slabs of lookahead.
+// and a fifth wave touching the weight lines 3 to 12 slabs ahead of the copies made every shape slower: HBM is
+// not what the copies wait for.  With the copies of W taken out the kernel still takes 29 us of 54 (gate|up,
+// warm), with those of X taken out 48: a 64-column tile copies all 128 rows of X again (16 KB per slab next to
+// 8 KB of weights), so the L2 -> LDS stream carries three times the weight bytes with two slabs of lookahead.
+// Hence the 128-column form below for wide matrices: 31 us for the same product.
 #include "kernels.h"
 
 namespace {
 
-constexpr int BM = 128, BN = 64, BK = 64;
-constexpr int kThreads = 256;
+// A workgroup is NH groups of 4 waves; group h owns output columns 64 h .. 64 h + 63 of a 128 x 64 NH tile and all
+// groups share the tile's X slab.  NH = 1: three stages of 24 KB, two workgroups per compute unit.  NH = 2: four
+// stages of 32 KB, one workgroup of 8 waves: X is copied once for 128 columns instead of twice and the copies run
+// three slabs ahead instead of two -- for wide matrices (many column tiles); narrow ones keep NH = 1, which gives
+// twice as many workgroups to cut K among.
+constexpr int BM = 128, BK = 64;
 constexpr int kXBytes = BM * BK * 2;   // 16 KB
-constexpr int kWBytes = BN * BK * 2;   // 8 KB
-constexpr int kStageBytes = kXBytes + kWBytes;
-constexpr int kPartFloats = BM * BN;   // partial sums of one K part of one tile
+constexpr int kWBytes = 64 * BK * 2;   // 8 KB per group of 64 columns
+constexpr int kWideMinSlabs = 40;
 
 struct SkinnyArgs {
   const unsigned short* X;
@@ -42,35 +47,40 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, -1, 0x00020000);
 }
 
-constexpr int kWaitVm0 = 0x0070, kWaitVm6 = 0x0076;
+constexpr int kWaitVm0 = 0x0070, kWaitVm6 = 0x0076, kWaitVm8 = 0x0078;
 #define SX_WAIT_BARRIER(IMM)              \
   asm volatile("" ::: "memory");          \
   __builtin_amdgcn_s_waitcnt(IMM);        \
   __builtin_amdgcn_s_barrier();           \
   asm volatile("" ::: "memory");
 
-template <int MODE>
-__global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArgs a) {
+template <int MODE, int NH>
+__global__ __launch_bounds__(256 * NH, 3 - NH) void gemm_skinny_bf16_kernel(SkinnyArgs a) {
+  constexpr int BN = 64 * NH;
+  constexpr int kStageBytes = kXBytes + NH * kWBytes;
+  constexpr int kPartFloats = BM * BN;   // partial sums of one K part of one tile
+  constexpr int kXCopies = 4 / NH;       // copy instructions (1 KB each) per wave and slab: X, then 2 for W
   // one array per stage: X rows then W rows, 128 bytes each, 16-byte chunk c of row r at position c ^ ((r >> 1) & 7)
   __shared__ __attribute__((aligned(1024))) unsigned char st0[kStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char st1[kStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char st2[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char st3[NH == 2 ? kStageBytes : 1024];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wh = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
   const int l16 = lane & 15, lq = lane >> 4;
   const int tile_n = blockIdx.x / a.split, kpart = blockIdx.x % a.split;
 
-  // ---- copies: instruction t of wave w fills X rows 32 w + 8 t .. + 7 (t < 4) or W rows 16 w + 8 t .. + 7 (t < 2)
+  // ---- copies: instruction t of wave w fills X rows 8 (kXCopies w + t) .. + 7 or W rows 16 w + 8 t .. + 7 (t < 2)
   const __amdgpu_buffer_rsrc_t xres = make_rsrc(a.X);
   const __amdgpu_buffer_rsrc_t wres0 = make_rsrc(a.W0), wres1 = make_rsrc(a.W1), wres2 = make_rsrc(a.W2);
   __amdgpu_buffer_rsrc_t wres[2];
   int xoff[4], woff[2];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < kXCopies; ++t) {
     const int cchunk = (lane & 7) ^ ((4 * (t & 1) + (lane >> 4)) & 7);
-    int m = 32 * wave + 8 * t + (lane >> 3);
+    int m = 8 * (kXCopies * wave + t) + (lane >> 3);
     m = m < a.M ? m : a.M - 1;
     xoff[t] = (int)(((unsigned)m * (unsigned)a.K + cchunk * 8) * 2u);
   }
@@ -102,13 +112,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
 #define SX_COPY(STG_, SLAB_)                                                                                     \
   {                                                                                                              \
     const int so = (SLAB_) * (BK * 2);                                                                           \
-    _Pragma("unroll") for (int t = 0; t < 4; ++t) __builtin_amdgcn_raw_ptr_buffer_load_lds(                      \
-        xres, (lds_void_ptr)(STG_ + wave * 4096 + t * 1024), 16, xoff[t], so, 0, 0);                             \
+    _Pragma("unroll") for (int t = 0; t < kXCopies; ++t) __builtin_amdgcn_raw_ptr_buffer_load_lds(               \
+        xres, (lds_void_ptr)(STG_ + (kXCopies * wave + t) * 1024), 16, xoff[t], so, 0, 0);                       \
     _Pragma("unroll") for (int t = 0; t < 2; ++t) __builtin_amdgcn_raw_ptr_buffer_load_lds(                      \
         wres[t], (lds_void_ptr)(STG_ + kXBytes + wave * 2048 + t * 1024), 16, woff[t], so, 0, 0);                \
   }
 
-  // acc[i][j]: W rows (output columns) 32 wn + 16 i .. + 15, X rows (output rows) 64 wm + 16 j .. + 15
+  // acc[i][j]: W rows (output columns) 64 wh + 32 wn + 16 i .. + 15, X rows (output rows) 64 wm + 16 j .. + 15
   f32x4 acc[2][4];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -118,13 +128,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
   const int fsw = (l16 >> 1) & 7;
   const int xrow = (wm * 64 + l16) * (BK * 2);
-  const int wrow = kXBytes + (wn * 32 + l16) * (BK * 2);
+  const int wrow = kXBytes + (wh * 64 + wn * 32 + l16) * (BK * 2);
   const int kc[2] = {(lq ^ fsw) << 4, ((4 + lq) ^ fsw) << 4};
 
 // "+v": the accumulators stay where they are (see the wide kernel); statements are volatile, order as written
 #define SX_MFMA(ACC, A, B) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(A), "v"(B));
 #define SX_SLAB(STG_, STG_F, SLAB_F)                                                                             \
-  SX_WAIT_BARRIER(kWaitVm6)                                                                                      \
+  SX_WAIT_BARRIER(NH == 1 ? kWaitVm6 : kWaitVm8)                                                                 \
   SX_COPY(STG_F, SLAB_F)                                                                                         \
   _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                             \
     bf16x8 fx[4], fw[2];                                                                                         \
@@ -142,17 +152,33 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
   const int nb_all = a.K / BK;
   const int first = kpart * nb_all / a.split;
   const int NB = (kpart + 1) * nb_all / a.split - first, last = first + NB - 1;
+  // (NH = 2: four stages, the copies of the next two slabs may stay in flight, those of the third go out)
   SX_COPY(st0, first)
   SX_COPY(st1, min(first + 1, last))
   int s = 0;
-  for (; s + 3 <= NB; s += 3) {
-    SX_SLAB(st0, st2, min(first + s + 2, last))
-    SX_SLAB(st1, st0, min(first + s + 3, last))
-    SX_SLAB(st2, st1, min(first + s + 4, last))
-  }
-  if (s < NB) {
-    SX_SLAB(st0, st2, last)
-    if (s + 1 < NB) { SX_SLAB(st1, st0, last) }
+  if (NH == 1) {
+    for (; s + 3 <= NB; s += 3) {
+      SX_SLAB(st0, st2, min(first + s + 2, last))
+      SX_SLAB(st1, st0, min(first + s + 3, last))
+      SX_SLAB(st2, st1, min(first + s + 4, last))
+    }
+    if (s < NB) {
+      SX_SLAB(st0, st2, last)
+      if (s + 1 < NB) { SX_SLAB(st1, st0, last) }
+    }
+  } else {
+    SX_COPY(st2, min(first + 2, last))
+    for (; s + 4 <= NB; s += 4) {
+      SX_SLAB(st0, st3, min(first + s + 3, last))
+      SX_SLAB(st1, st0, min(first + s + 4, last))
+      SX_SLAB(st2, st1, min(first + s + 5, last))
+      SX_SLAB(st3, st2, min(first + s + 6, last))
+    }
+    if (s < NB) {
+      SX_SLAB(st0, st3, last)
+      if (s + 1 < NB) { SX_SLAB(st1, st0, last) }
+      if (s + 2 < NB) { SX_SLAB(st2, st1, last) }
+    }
   }
   __builtin_amdgcn_s_waitcnt(kWaitVm0);  // copies past the end of K must land before the LDS is released
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");  // the matrix pipe's last results (hand-written MFMAs)
@@ -209,7 +235,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
   const bool vec = (a.N & 3) == 0;
   if (MODE == SX_GEMM_SWIGLU) {
     unsigned short* Y = static_cast<unsigned short*>(a.Y);
-    const int f = tile_n * (BN / 2) + wn * 16 + 4 * lq;
+    const int f = tile_n * (BN / 2) + (2 * wh + wn) * 16 + 4 * lq;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int m = wm * 64 + 16 * j + l16;
@@ -235,7 +261,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
   } else if (vec && tile_n * BN + BN <= a.N) {
     // whole column tile: the residual of all 8 blocks is requested before the first add (rows past M read row M - 1
     // and store nothing); block by block the epilogue was 8 memory round trips long
-    float* Yb = static_cast<float*>(a.Y) + (tile_n * BN + wn * 32 + 4 * lq);
+    float* Yb = static_cast<float*>(a.Y) + (tile_n * BN + wh * 64 + wn * 32 + 4 * lq);
     f32x4 r[4][2];
     if (MODE == SX_GEMM_RESIDUAL) {
 #pragma unroll
@@ -262,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_skinny_bf16_kernel(SkinnyArg
       const int m = wm * 64 + 16 * j + l16;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int n = tile_n * BN + wn * 32 + 16 * i + 4 * lq;
+        const int n = tile_n * BN + wh * 64 + wn * 32 + 16 * i + 4 * lq;
         if (m >= a.M || n >= a.N) continue;
         float* y = Y + (size_t)m * a.N + n;
         if (vec) {
@@ -305,38 +331,57 @@ int sx_launch_gemm_skinny_bf16(const void* X, const void* W0, const void* W1, co
   a.Y = Y;
   a.M = M;
   a.K = K;
+  int cols;  // rows of W that a launch walks (gate and up both count)
   if (mode == SX_GEMM_SWIGLU) {
     if (n1 != n0 || n2 != 0 || !W1) return SX_ERR_SHAPE;
     a.N = n0;
-    a.tilesN = (n0 + BN / 2 - 1) / (BN / 2);
+    cols = 2 * n0;
   } else {
     a.N = n0 + n1 + n2;
-    a.tilesN = (a.N + BN - 1) / BN;
+    cols = a.N;
   }
   // Cut K only while there are fewer tiles than compute units (measured: with a tile per unit or more the extra
   // parts cost more in partial sums and short K loops than they gain), parts of at least 4 slabs, and only as
-  // far as the caller's memory for partial sums (and its 256 counters) goes
-  a.split = 1;
+  // far as the caller's memory for partial sums (and its 256 counters) goes.
+  // 128-column tiles (8 waves) where they need no cut or the parts of the cut stay long (40 slabs: the 7B QKV
+  // projection, cut in two parts of 32, is better off with 192 uncut 64-column tiles; the 70B one, three parts of
+  // 42, is not); otherwise twice as many 64-column tiles.
+  const int slots = sx_compute_units(), nb = K / BK;
+  auto plan = [&](int bn, int& tiles, int& split) {
+    tiles = (cols + bn - 1) / bn;
+    split = 1;
+    if (split_ws && tiles <= 256 && 2 * tiles <= slots) {
+      split = slots / tiles;
+      if (split > 8) split = 8;
+      while (split > 1 && nb / split < 4) --split;
+      if (split_ws_bytes < 1024 + (size_t)tiles * split * BM * bn * sizeof(float)) split = 1;
+    }
+  };
+  int nh = 1, tiles = 0, split = 1;
+  if (cols >= 128) {
+    plan(128, tiles, split);
+    if (split == 1 ? 2 * tiles > slots : nb / split >= kWideMinSlabs) nh = 2;
+  }
+  if (nh == 1) plan(64, tiles, split);
+  a.tilesN = tiles;
+  a.split = split;
   a.part = nullptr;
   a.part_cnt = nullptr;
-  const int slots = sx_compute_units(), nb = K / BK;
-  if (split_ws && a.tilesN <= 256 && 2 * a.tilesN <= slots) {
-    int split = slots / a.tilesN;
-    if (split > 8) split = 8;
-    while (split > 1 && nb / split < 4) --split;
-    if (split > 1 && split_ws_bytes >= 1024 + (size_t)a.tilesN * split * kPartFloats * sizeof(float)) {
-      a.split = split;
-      a.part_cnt = static_cast<int*>(split_ws);
-      a.part = reinterpret_cast<float*>(static_cast<char*>(split_ws) + 1024);
-    }
+  if (split > 1) {
+    a.part_cnt = static_cast<int*>(split_ws);
+    a.part = reinterpret_cast<float*>(static_cast<char*>(split_ws) + 1024);
   }
   const int grid = a.tilesN * a.split;
+#define SX_GO(MODE_)                                                                    \
+  if (nh == 2) gemm_skinny_bf16_kernel<MODE_, 2><<<grid, 512, 0, st>>>(a);              \
+  else gemm_skinny_bf16_kernel<MODE_, 1><<<grid, 256, 0, st>>>(a);
   switch (mode) {
-    case SX_GEMM_STORE: gemm_skinny_bf16_kernel<SX_GEMM_STORE><<<grid, kThreads, 0, st>>>(a); break;
-    case SX_GEMM_RESIDUAL: gemm_skinny_bf16_kernel<SX_GEMM_RESIDUAL><<<grid, kThreads, 0, st>>>(a); break;
-    case SX_GEMM_SWIGLU: gemm_skinny_bf16_kernel<SX_GEMM_SWIGLU><<<grid, kThreads, 0, st>>>(a); break;
+    case SX_GEMM_STORE: SX_GO(SX_GEMM_STORE) break;
+    case SX_GEMM_RESIDUAL: SX_GO(SX_GEMM_RESIDUAL) break;
+    case SX_GEMM_SWIGLU: SX_GO(SX_GEMM_SWIGLU) break;
     default: return SX_ERR_SHAPE;
   }
+#undef SX_GO
   SX_LAUNCH_CHECK();
   return SX_OK;
 }
