@@ -72,8 +72,10 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {  // round to nea
   __bf16 h = (__bf16)f;
   return (uint32_t)__builtin_bit_cast(unsigned short, h);
 }
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+typedef float sx_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {  // both roundings in one v_cvt_pk_bf16_f32
+  const sx_f32x2 t = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(t, bf16x2));
 }
 
 // silu(g) * u where the product is rounded to bf16 right after (the SwiGLU epilogues of the bf16 paths): the

@@ -450,6 +450,21 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
         }
       }
     }
+  } else if (MODE == SX_GEMM_SWIGLU && vec && tile_m * BM + BM <= a.M && tile_n * (BN / 2) + BN / 2 <= a.N) {
+    // a whole tile: no edge tests between the stores
+    unsigned short* Yb = static_cast<unsigned short*>(a.Y) + (size_t)(mbase + l16) * a.N + (tile_n * (BN / 2) + wn * 64 + 4 * lq);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii) {
+        float h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = silu_mul_bf16_bound(acc[2 * ii][j][e], acc[2 * ii + 1][j][e]);
+        u32x2 v;
+        v[0] = pack_bf16x2(h[0], h[1]);
+        v[1] = pack_bf16x2(h[2], h[3]);
+        *reinterpret_cast<u32x2*>(Yb + (size_t)(16 * j) * a.N + 16 * ii) = v;
+      }
   } else if (MODE == SX_GEMM_SWIGLU) {
     unsigned short* Y = static_cast<unsigned short*>(a.Y);
 #pragma unroll

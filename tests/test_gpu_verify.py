@@ -333,8 +333,10 @@ def test_commit_kv_bf16_gathers_path_rows(sx):
 # bf16 building blocks
 # ------------------------------------------------------------------------------------------------
 
+# (100, 20000, 192) and (128, 17000, 64): few rows and a wide matrix, the 128-column form of the narrow kernel, ragged last tile
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 256), (300, 200, 128), (1, 1000, 192), (520, 768, 4096),
-                                   (128, 4096, 11008), (33, 72, 64), (100, 130, 320)])
+                                   (128, 4096, 11008), (33, 72, 64), (100, 130, 320), (100, 20000, 192),
+                                   (128, 17000, 64)])
 def test_gemm_bf16_store_and_residual(sx, M, N, K):
     X = wl.hash_normal(1, (M, K), dtype=torch.bfloat16)
     W = wl.hash_normal(2, (N, K), std=0.05, dtype=torch.bfloat16)
@@ -387,7 +389,8 @@ def test_gemm_w4a16(sx, M, N, K, group, split):
     assert np.abs(Y.cpu().double().numpy() - 2 * ref).max() <= 2 * tol
 
 
-@pytest.mark.parametrize("M,F,K", [(256, 128, 64), (300, 200, 256), (100, 11008, 128), (128, 96, 4096), (7, 40, 64)])
+@pytest.mark.parametrize("M,F,K", [(256, 128, 64), (300, 200, 256), (100, 11008, 128), (128, 96, 4096), (7, 40, 64),
+                                   (77, 9000, 128)])
 def test_gemm_bf16_swiglu(sx, M, F, K):
     X = wl.hash_normal(3, (M, K), dtype=torch.bfloat16)
     Wg = wl.hash_normal(4, (F, K), std=0.1, dtype=torch.bfloat16)
@@ -444,8 +447,11 @@ def test_gemm_bf16_few_tiles_cut_along_k(sx, M, N, K, mode):
 
 # the last three shapes give more output tiles than the chip has compute units with a small remainder: the
 # remainder tiles are cut along K and their partial sums added up by the last workgroup to arrive
+# (256, 2048, 16, 4) and (512, 1024, 8, 8): fewer tiles than half the compute units, all of them cut along K;
+# (77, 8192, 64, 8): few rows, three stacked matrices through the 128-column form of the narrow kernel, K cut in 3
 @pytest.mark.parametrize("T,d,Hq,Hkv", [(256, 256, 2, 2), (300, 512, 4, 1), (77, 1024, 8, 2),
-                                        (2048, 2048, 64, 8), (2048, 2048, 64, 1), (2304, 1024, 64, 8)])
+                                        (2048, 2048, 64, 8), (2048, 2048, 64, 1), (2304, 1024, 64, 8),
+                                        (256, 2048, 16, 4), (512, 1024, 8, 8), (77, 8192, 64, 8)])
 def test_qkv_projection_with_rotary_epilogue(sx, T, d, Hq, Hkv):
     """The QKV GEMM that rotates and splits into heads in its epilogue, against the oracle's rope applied to
     fp64 projections (rows beyond a tile, GQA, head columns that cross tile boundaries)."""
