@@ -80,7 +80,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]):
 // all LDS reads done, at most N vector-memory operations outstanding.
-constexpr int kWaitVm0 = 0x0070, kWaitVm2 = 0x0072, kWaitVm16 = 0x4070;
+constexpr int kWaitVm0 = 0x0070, kWaitVm2 = 0x0072, kWaitVm16 = 0x4070, kWaitVm18 = 0x4072;
 
 // Wait until this wave's LDS reads are done and at most the given number of copies are in flight, then
 // meet the other waves.  The barrier intrinsic alone does not order memory operations for the compiler,
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     SX_READS_B(STG_N, fx0, fw0, kc0, r)                                                                        \
   }                                                                                                            \
   if (PF) { /* youngest in the queue: the barrier's wait lets these two loads stay in flight */                \
-    asm volatile("" ::"v"(pfx), "v"(pfw));                                                                     \
+    asm volatile("" ::"v"(pfx), "v"(pfw) : "memory"); /* and they stay behind the copies issued above */       \
     const int pso = min((SO_) + kPfDist * (BK * 2), last * (BK * 2));                 \
     pfx = __builtin_amdgcn_raw_buffer_load_b32(xres, pfxoff, pso, 0);                                          \
     pfw = __builtin_amdgcn_raw_buffer_load_b32(pfwres, pfwoff, pso, 0);                                        \
@@ -309,7 +309,17 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
   const int NB = (kpart + 1) * nb_all / ksplit - first, last = first + NB - 1;
   SX_COPY(stA, first)
   SX_COPY(stB, min(first + 1, last))
-  SX_WAIT_BARRIER(kWaitVm16)
+  if (PF) {
+    // The in-loop barriers let the two youngest operations stay in flight, taking them to be a slab's two
+    // prefetch loads.  Before the first slab has issued any, the two youngest would be the last copies into the
+    // second stage (X and W rows 56..63 of each wave's share), read by the first slab's second phase: so the
+    // prologue issues a pair of prefetch loads of its own.  (Without them those rows were occasionally stale.)
+    asm volatile("" ::: "memory");
+    const int pso = min(first + 2, last) * (BK * 2);
+    pfx = __builtin_amdgcn_raw_buffer_load_b32(xres, pfxoff, pso, 0);
+    pfw = __builtin_amdgcn_raw_buffer_load_b32(pfwres, pfwoff, pso, 0);
+  }
+  SX_WAIT_BARRIER(PF ? kWaitVm18 : kWaitVm16)
   _Pragma("unroll") for (int i = 0; i < 8; ++i) { SX_READW(stA, fw0, i, kc0) SX_READX(stA, fx0, i, kc0) }
   int s = 0;
   for (; s + 2 <= NB; s += 2) {
@@ -402,17 +412,37 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     // the same for the whole wave.  Column 16 i + 4 lq + e and column + 64 (block i + 4, same lane and
     // register) are the pair the rotary embedding turns by the row's angle (Alg. 1: node at position
     // P + depth); the values are rounded to bf16 once, after the rotation.
-    // (The table loads of a row block sit behind the stores of the one before, so every row block waits for a
-    // memory round trip.  Requesting them a row block ahead in a second set of 32 registers was tried: the tiles
-    // that come out of the K-split reduction then gave different bits from run to run -- cause not found, the
-    // registers of this kernel are all in use at that point -- and the change was taken out again;
-    // tests/test_gpu_verify.py repeats this projection in fresh workspaces to guard the property.)
+    // The tile's 256 rows of the cos/sin table (512 bytes each) are first copied into the LDS the K loop has
+    // left free -- rows 0..127 into the first stage's array, 128..255 into the second's -- and read from there:
+    // loaded from memory row block by row block, every load waited behind the stores of the block before (one
+    // counter covers both on this chip), 32 memory round trips per tile.  16-byte chunk c of table row r sits at
+    // chunk position (c & 16) | ((c ^ r) & 15) of its 512 bytes: the 16 rows a read instruction covers fall on 16
+    // bank groups.
     const int head = tile_n * 2 + wn;
     const bool is_v = head >= a.hq + a.hkv;
     unsigned short* dst = head < a.hq ? a.q : is_v ? a.v : a.k;
     const int hh = head < a.hq ? head : is_v ? head - a.hq - a.hkv : head - a.hq;
     const int nh = head < a.hq ? a.hq : a.hkv;
+    if (tile_n * 2 < a.hq + a.hkv) {  // the tile holds a query or key head (same answer in all four waves)
+      __syncthreads();  // every wave is past its last fragment reads of the stages
+      const __amdgpu_buffer_rsrc_t cres = make_rsrc(a.cs);
+#pragma unroll
+      for (int t = 0; t < 32; ++t) {  // copy t of wave w: table rows 2 (16 w + t % 16) and + 1 of half t / 16
+        const int r = 2 * (16 * wave + (t & 15)) + (lane >> 5);
+        int m = tile_m * BM + (t >> 4) * 128 + r;
+        m = m < a.M ? m : a.M - 1;
+        const int pch = lane & 31, c = (pch & 16) | ((pch ^ r) & 15);
+        unsigned char* stg = (t >> 4) ? stB : stA;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(cres, (lds_void_ptr)(stg + (16 * wave + (t & 15)) * 1024), 16,
+                                                 (int)((unsigned)m * 512u + (unsigned)c * 16u), 0, 0, 0);
+      }
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
     if (head < a.hq + 2 * a.hkv) {
+      const unsigned char* tb = wm ? stB : stA;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int m = mbase + 16 * j + l16;
@@ -422,29 +452,33 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             u32x2 o;
-            o[0] = f32_to_bf16_bits(acc[i][j][0]) | (f32_to_bf16_bits(acc[i][j][1]) << 16);
-            o[1] = f32_to_bf16_bits(acc[i][j][2]) | (f32_to_bf16_bits(acc[i][j][3]) << 16);
+            o[0] = pack_bf16x2(acc[i][j][0], acc[i][j][1]);
+            o[1] = pack_bf16x2(acc[i][j][2], acc[i][j][3]);
             *reinterpret_cast<u32x2*>(y + 16 * i) = o;
           }
         } else {
-          const f32x4* t4 = reinterpret_cast<const f32x4*>(a.cs + (size_t)m * 64 + 4 * lq);
+          const int r = 16 * j + l16;
+          const unsigned char* trow = tb + r * 512;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const f32x4 c01 = t4[8 * i], c23 = t4[8 * i + 1];  // (cos, sin) of pairs 16 i + 4 lq + 0..3
+            // (cos, sin) of pairs 16 i + 4 lq + 0..3: chunks 8 i + 2 lq and + 1 of the row
+            const int c0 = 8 * i + 2 * lq;
+            const f32x4 c01 = *reinterpret_cast<const f32x4*>(trow + (((c0 & 16) | ((c0 ^ r) & 15)) << 4));
+            const f32x4 c23 = *reinterpret_cast<const f32x4*>(trow + ((((c0 + 1) & 16) | (((c0 + 1) ^ r) & 15)) << 4));
             const float cs_[4] = {c01[0], c01[2], c23[0], c23[2]}, sn_[4] = {c01[1], c01[3], c23[1], c23[3]};
-            uint32_t lo[4], hi[4];
+            float lo[4], hi[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float x0 = acc[i][j][e], x1 = acc[i + 4][j][e];
-              lo[e] = f32_to_bf16_bits(x0 * cs_[e] - x1 * sn_[e]);
-              hi[e] = f32_to_bf16_bits(x0 * sn_[e] + x1 * cs_[e]);
+              lo[e] = x0 * cs_[e] - x1 * sn_[e];
+              hi[e] = x0 * sn_[e] + x1 * cs_[e];
             }
             u32x2 o;
-            o[0] = lo[0] | (lo[1] << 16);
-            o[1] = lo[2] | (lo[3] << 16);
+            o[0] = pack_bf16x2(lo[0], lo[1]);
+            o[1] = pack_bf16x2(lo[2], lo[3]);
             *reinterpret_cast<u32x2*>(y + 16 * i) = o;
-            o[0] = hi[0] | (hi[1] << 16);
-            o[1] = hi[2] | (hi[3] << 16);
+            o[0] = pack_bf16x2(hi[0], hi[1]);
+            o[1] = pack_bf16x2(hi[2], hi[3]);
             *reinterpret_cast<u32x2*>(y + 64 + 16 * i) = o;
           }
         }
@@ -664,7 +698,7 @@ int sx_launch_gemm_qkv_rope_bf16(const void* X, const void* Wq, const void* Wk, 
                                  size_t split_ws_bytes, hipStream_t st) {
   if (M < 1 || K < BK || K % BK != 0 || hq < 1 || hkv < 1) return SX_ERR_SHAPE;
   if (!sx_operand_fits_u32(M, 2ll * K) || !sx_operand_fits_u32(128ll * hq, 2ll * K) ||
-      !sx_operand_fits_u32(128ll * hkv, 2ll * K))
+      !sx_operand_fits_u32(128ll * hkv, 2ll * K) || !sx_operand_fits_u32(M, 512))  // the table: 512 bytes per row
     return SX_ERR_SHAPE;
   GemmArgs a;
   a.X = static_cast<const unsigned short*>(X);
