@@ -65,5 +65,8 @@ def test_host_side_errors_return_codes(sx):
     assert L.sx_gemm_bf16(one, one, None, one, 256, 262144, 8192, 0, None) == -2  # W of 4 GiB: 32-bit offsets would wrap
     assert L.sx_gemm_bf16(one, one, None, one, 64, 262144, 8192, 0, None) == -2   # the same through the narrow-tile kernel
     assert L.sx_gemm_bf16(one, one, None, one, 65536, 64, 32768, 1, None) == -2   # X of 4 GiB
+    assert L.sx_gemm_bf16_workspace() >= 1024 + 256 * 256 * 4
+    assert L.sx_gemm_bf16_ws(one, one, None, one, 8, 8, 128, 0, C.c_void_p(264), 1 << 20, None) == -3   # misaligned workspace
+    assert L.sx_gemm_bf16_ws(one, one, None, one, 8, 8, 100, 0, one, 1 << 20, None) == -2               # K % 64 != 0
     assert L.sx_verify_tree(None, None, None, 0, one, one, 4, one, None, None, one, 1 << 20, None) == -1
     assert L.sx_row_logsoftmax_topk(one, 4, 100, 300, one, one, None) == -2
