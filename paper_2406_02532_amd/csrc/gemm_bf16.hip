@@ -294,13 +294,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     pfx = __builtin_amdgcn_raw_buffer_load_b32(xres, pfxoff, pso, 0);                                          \
     pfw = __builtin_amdgcn_raw_buffer_load_b32(pfwres, pfwoff, pso, 0);                                        \
   }
-#ifndef SX_SPLIT_BATCH
-#define SX_SPLIT_BATCH 16
-#endif
-#ifndef SX_COPY_ROWS
-#define SX_COPY_ROWS 8
-#endif
-  constexpr int kCopyRows = SX_COPY_ROWS;
+  constexpr int kCopyRows = 8;
 
   // The loop body is branch-free: past the end of K it copies the last slab again, into a stage nobody
   // reads any more, and reads fragments nobody uses.
@@ -376,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmArgs a) {
     }
     __syncthreads();
     if (!s_last) return;
-    constexpr int kBatch = SX_SPLIT_BATCH;
+    constexpr int kBatch = 16;
     // Read back in batches of kBatch blocks per part, all loads of a batch in flight together: one memory round
     // trip per batch and part instead of one per block (a block at a time, the 64 dependent round trips were
     // most of what the split cost).  Parts are added in part order whatever the batch size.

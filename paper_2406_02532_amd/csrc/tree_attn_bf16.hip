@@ -70,20 +70,13 @@ __device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {  // one v_
   return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
-#ifdef SX_ATT_NO_SB
-#define SX_ATT_SCHED_BARRIER
-#else
+// nothing is scheduled across this point (keeps the fragment reads of a tile ahead of its first MFMA)
 #define SX_ATT_SCHED_BARRIER __builtin_amdgcn_sched_barrier(0);
-#endif
 // maximum of a value over the lane pair (l, l ^ 32): one lane-half swap inside the vector unit, no LDS round trip
 __device__ __forceinline__ float pair_max(float x) {
-#ifdef SX_ATT_BPERMUTE
-  return fmaxf(x, __shfl_xor(x, 32, 64));
-#else
   const unsigned u = __float_as_uint(x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-#endif
 }
 #define SX_ATT_XMAX(x) pair_max(x)
 // s_waitcnt: all vector-memory operations (the copies) and all LDS reads of this wave done
@@ -112,13 +105,11 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_bf16_kernel(AttnArgs a)
   // before the next: the K/V rows of a head are then fetched into one L2 only, and the workgroups that
   // run there side by side all read them.
   int tile = blockIdx.x, kvh = blockIdx.y;
-#ifndef SX_ATT_NO_XCD
   if ((gridDim.y & 7) == 0) {
     const int lin = blockIdx.x + gridDim.x * blockIdx.y, j = lin >> 3;
     tile = j % gridDim.x;
     kvh = ((j / gridDim.x) << 3) + (lin & 7);
   }
-#endif
   const int n0 = tile * a.npt;
 
   // ---- this lane's query row -----------------------------------------------------------------------
