@@ -176,7 +176,7 @@ def main():
     # token of the next node along the path to the deepest leaf) make accept_walk take one step per tree level
     # and commit_kv copy that many rows in every layer; both are timed with HIP events.
     walk = walk_block(sx, wl, torch, np, dev, cfg, tok, par, tok_d, par_d, pk, pv, tree_k, tree_v, P, temperature, top_p)
-    sweep = t_sweep(sx, wl, torch, np, dev, cfg, mw, pk, pv, P, k_tree, T) if args.workload == "C5" else None
+    sweep = t_sweep(sx, wl, torch, np, dev, cfg, mw, w, pk, pv, P, k_tree, T) if args.workload == "C5" else None
     if args.calibration_copy:
         src = torch.full((CAL_COPY_BYTES // 4,), 1.0, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -319,32 +319,49 @@ def walk_block(sx, wl, torch, np, dev, cfg, tok, par, tok_d, par_d, pk, pv, tree
                 rows_committed_per_layer=n, logits="crafted: N(0,1) plus 30 on the next token of the path to the deepest leaf")
 
 
-def t_sweep(sx, wl, torch, np, dev, cfg, mw, pk, pv, P, k_tree, T_full):
+def t_sweep(sx, wl, torch, np, dev, cfg, mw, w, pk, pv, P, k_tree, T_full):
     """Forward time against tree size (the paper's Fig. 1, right, asks how the target's forward time grows with the
-    number of input tokens): sx_verify_tree alone on best-first trees of 256, 1024 and 2048 nodes, same model and prefix."""
-    out = []
-    for T in (256, 1024, T_full):
+    number of input tokens): sx_verify_tree alone on best-first trees of 128 to 2048 nodes, same model and prefix.
+    Then the same target with its decoder layers in 4 bits (Sect. 5; random codes, group 128) at the two ends of the
+    range: up to 128 nodes the 4-bit GEMM kernel runs, above it the layer is dequantised into a bf16 scratch copy."""
+    def forward_ms(weights, T, reps=3):
         tok, par, _ = wl.gen_best_first_tree(T, k_tree, cfg.vocab, seed=3)
         tok_d, par_d = torch.from_numpy(tok).to(dev), torch.from_numpy(par).to(dev)
         logits = torch.empty((T, cfg.vocab), dtype=torch.float32, device=dev)
-        ws = torch.empty(sx.verify_tree_workspace(cfg, P, T), dtype=torch.uint8, device=dev)
+        ws = torch.empty(weights.workspace_bytes(P, T), dtype=torch.uint8, device=dev)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 3
         for r in range(reps + 1):
             if r == 1:
                 e0.record()
-            sx.verify_tree(mw, pk, pv, tok_d, par_d, logits_out=logits, workspace=ws, P=P)
+            sx.verify_tree(weights, pk, pv, tok_d, par_d, logits_out=logits, workspace=ws, P=P)
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        assert sx.check_status(ws) == 0
+        return e0.elapsed_time(e1) / reps, par
+
+    d, F, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+    Nq, Nkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    out = []
+    for T in (128, 256, 1024, T_full):
+        ms, par = forward_ms(mw, T)
         depth = np.zeros(T, dtype=np.int64)
         for i in range(T):
             depth[i] = 0 if par[i] < 0 else depth[par[i]] + 1
-        d, F, V = cfg.d_model, cfg.d_ffn, cfg.vocab
-        Nq, Nkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
         flop = cfg.n_layers * (2.0 * T * d * (Nq + 2 * Nkv) + 2.0 * T * Nq * d + 6.0 * T * d * F
                                + 4.0 * Nq * float((P + depth + 1).sum())) + 2.0 * T * d * V
-        out.append(dict(T=T, ms=round(ms, 3), tokens_per_s=round(T / ms * 1e3, 1), tflops=round(flop / ms / 1e9, 1)))
+        out.append(dict(T=T, weights="bf16", ms=round(ms, 3), tokens_per_s=round(T / ms * 1e3, 1), tflops=round(flop / ms / 1e9, 1)))
+    free, _ = torch.cuda.mem_get_info()
+    need = cfg.n_layers * (d * (Nq + 2 * Nkv) + Nq * d + 3 * d * F) * 0.53 + 8e9   # codes, scales, zero points, scratch
+    if free > need:
+        w4 = dict(embed=w["embed"], lm_head=w["lm_head"], final_norm=w["final_norm"],
+                  layers=[{n: lw[n] for n in ("attn_norm", "ffn_norm")} for lw in w["layers"]],
+                  layers_w4=wl.gen_w4_layers(cfg, 128, seed=7, device=dev), w4_group=128)
+        mw4 = sx.ModelWeights(cfg, w4)
+        for T in (128, T_full):
+            ms, _ = forward_ms(mw4, T)
+            out.append(dict(T=T, weights="4-bit decoder layers (group 128)", ms=round(ms, 3), tokens_per_s=round(T / ms * 1e3, 1)))
+        del mw4, w4
+        torch.cuda.empty_cache()
     return out
 
 
